@@ -1,0 +1,150 @@
+/*
+ * hot.h - C ABI of the MI355X (gfx950) implementation of the HOT linear-layer
+ * backward pass (arxiv 2503.21261, "HOT: Hadamard-based Optimized Training").
+ *
+ * Notation (Sec. 4.1, Eq. 7-8): x [L x I] input activation, w [O x I] weight,
+ * y = x.w^T [L x O], g_y [L x O] output gradient,
+ *     g_x = g_y . w   [L x I]      g_w = g_y^T . x   [O x I].
+ * L is the flattened token index (batch x sequence), tiled consecutively in
+ * blocks of n for the token-direction transform.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers to row-major, contiguous buffers,
+ *     16-byte aligned, fp32 unless stated.  Pointers marked "host" are host
+ *     memory.  The caller owns every buffer; the library never allocates, frees
+ *     or keeps device memory between calls.
+ *   - `ws` is caller-provided device scratch of at least hot_workspace_bytes()
+ *     bytes (256-byte aligned).  Its contents after a call are the packed
+ *     operands of that call; the hot_debug_* calls decode them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return without synchronising, except
+ *     hot_select_quantizer, which waits for its own result.
+ *   - Errors are return codes; arguments are checked on the host before any
+ *     launch, so a failing call has launched nothing.  Inputs must be finite.
+ *   - Two calls that share a workspace or an output must be ordered by the
+ *     caller (same stream, or events).
+ */
+#ifndef HOT_H
+#define HOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HOT_OK = 0,
+  HOT_ERR_ARG = 1,        /* null pointer, bad enum, bad config field            */
+  HOT_ERR_SHAPE = 2,      /* a size the method or the int32 accumulators forbid  */
+  HOT_ERR_WORKSPACE = 3,  /* ws_bytes smaller than hot_workspace_bytes()         */
+  HOT_ERR_DEVICE = 4,     /* a HIP runtime call failed                           */
+  HOT_ERR_UNIMPLEMENTED = 5
+} hot_status;
+
+/* Sec. 5.2.2: granularity of the scale of the rotated g_y. */
+typedef enum { HOT_Q_PER_TENSOR = 0, HOT_Q_PER_TOKEN = 1 } hot_quantizer;
+
+/* Sec. 5.1: the paper's quantiser rounds pseudo-stochastically; nearest-even is
+ * offered so the half-step round-trip bound can be checked. */
+typedef enum { HOT_ROUND_NEAREST_EVEN = 0, HOT_ROUND_PSEUDO_STOCHASTIC = 1 } hot_rounding;
+
+typedef struct {
+  int32_t block;           /* n: WHT tile, 16 (paper, Supp. D) | 32 | 64                */
+  int32_t keep;            /* r: rows of each n-block kept by HLA on the g_w path,
+                              1..n (paper: 8 of 16, Supp. B)                          */
+  const int32_t* keep_idx; /* host, r distinct natural-order row indices in [0,n), or
+                              NULL = the r rows of lowest sequency, by increasing
+                              sequency (Sec. 3.3)                                     */
+  int32_t gx_bits;         /* 4 (paper, Sec. 5.1) | 8 (INT8 warm-up, Supp. B)         */
+  int32_t gw_bits;         /* 8 (Sec. 5.2)                                            */
+  int32_t rounding;        /* hot_rounding                                            */
+  float lqs_threshold;     /* 0.5 (Sec. 5.2.2)                                        */
+} hot_config;
+
+/* Fills *cfg with the paper's defaults: n = 16, r = 8, low-sequency rows, INT4 /
+ * INT8, pseudo-stochastic rounding, threshold 0.5. */
+void hot_default_config(hot_config* cfg);
+
+const char* hot_status_string(hot_status s);
+
+/* Bytes of the compressed activation buffer for x [L x I] (Sec. 5.2.1): a
+ * 256-byte header holding the scale, then L*r/n x I INT8 codes stored with the
+ * reduced token index contiguous (row pitch rounded up to 128 bytes).  Returns 0
+ * for an invalid config or shape. */
+size_t hot_act_buffer_bytes(const hot_config* cfg, int64_t L, int64_t I);
+
+/* Scratch bytes sufficient for every call below at this (L, O, I). 0 = invalid. */
+size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t I);
+
+/*
+ * Activation Buffer Compression, Sec. 5.2.1, run right after the forward pass:
+ *   x_hat = rows keep_idx of (H_n applied to every block of n consecutive tokens
+ *   of x), INT8 with one abs-max scale for the tensor.
+ * x: device [L x I] (in).  act_buf: device, hot_act_buffer_bytes() bytes (out).
+ * Requires L % n == 0, L*r/n <= 133144.
+ */
+hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_t L, int64_t I,
+                                   void* act_buf, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Activation-gradient path, Sec. 5.1 (Eq. 3-4 with Q = INT4):
+ *   g_x = dequant( Q(g_y.H^T) . Q(H.w) ),  H block-diagonal along O.
+ * g_y: device [L x O] (in); w: device [O x I] (in); g_x: device [L x I] (out).
+ * gy_quantizer: scale of the rotated g_y per token or per tensor (Sec. 4.3,
+ * 5.2.2); the rotated w always has one scale.  Requires O % n == 0.
+ */
+hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const float* w,
+                                  int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
+                                  float* g_x, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Weight-gradient path, Sec. 5.2 (Eq. 5 with INT8 operands):
+ *   g_w = dequant( Q(HLA(g_y))^T . x_hat ),  HLA along the token index L.
+ * g_y: device [L x O] (in); act_buf: what hot_compress_activation wrote for the
+ * same cfg, L, I (in); g_w: device [O x I] (out).  Requires L % n == 0.
+ */
+hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
+                                  int64_t L, int64_t O, int64_t I, float* g_w, void* ws,
+                                  size_t ws_bytes, void* stream);
+
+/*
+ * Layer-wise Quantizer Selection, Sec. 5.2.2, for one layer's calibration g_y:
+ * mean squared error between g_y and its rotated, gx_bits-quantised,
+ * de-rotated version with per-token and with per-tensor scales; per-token is
+ * chosen iff mse_tensor > 0 and (mse_tensor - mse_token) >= lqs_threshold *
+ * mse_tensor.  choice / mse_token / mse_tensor are HOST pointers (the two MSE
+ * pointers may be NULL).  Synchronises the stream.
+ */
+hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t L, int64_t O,
+                                hot_quantizer* choice, double* mse_token, double* mse_tensor,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* ---- parity views (not on the timed path): logical forms of packed data ---- */
+
+/* Compressed activation as row-major codes [L*r/n x I] and its scale [1]. */
+hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_buf, int64_t L,
+                                       int64_t I, int8_t* codes, float* scale, void* stream);
+
+/* Operands left in `ws` by the last hot_linear_backward_gx with these arguments:
+ * codes of the rotated g_y [L x O] and w [O x I] (row-major, one code per byte),
+ * scales of g_y ([L] per token, [1] per tensor) and of w [1], and the int32
+ * integer product [L x I] recomputed from those operands.  Any output may be
+ * NULL. */
+hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t L, int64_t O,
+                                 int64_t I, hot_quantizer gy_quantizer, int8_t* gy_codes,
+                                 float* gy_scales, int8_t* w_codes, float* w_scale, int32_t* acc,
+                                 void* stream);
+
+/* Operands left in `ws` by the last hot_linear_backward_gw: codes of HLA(g_y)
+ * [L*r/n x O] row-major, its scale [1], and the int32 product [O x I] recomputed
+ * from those codes and act_buf.  Any output may be NULL. */
+hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+                                 int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
+                                 float* gy_scale, int32_t* acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HOT_H */

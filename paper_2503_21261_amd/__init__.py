@@ -1,0 +1,235 @@
+"""Thin Python binding of libhot, the MI355X implementation of the HOT linear-layer
+backward pass (arxiv 2503.21261).
+
+Argument marshalling only: every step runs in the HIP kernels behind the C ABI
+declared in ``include/hot.h``; function names here are the C names.  torch is
+used for device memory and streams.  There is no CPU fallback: if the library
+has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhot.so")
+
+HOT_OK = 0
+HOT_ERR_ARG, HOT_ERR_SHAPE, HOT_ERR_WORKSPACE, HOT_ERR_DEVICE, HOT_ERR_UNIMPLEMENTED = 1, 2, 3, 4, 5
+HOT_Q_PER_TENSOR, HOT_Q_PER_TOKEN = 0, 1
+HOT_ROUND_NEAREST_EVEN, HOT_ROUND_PSEUDO_STOCHASTIC = 0, 1
+
+EXPORTS = (
+    "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
+    "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
+    "hot_select_quantizer", "hot_debug_unpack_activation", "hot_debug_gx_operands",
+    "hot_debug_gw_operands",
+)
+
+
+class hot_config(C.Structure):
+    _fields_ = [("block", C.c_int32), ("keep", C.c_int32), ("keep_idx", C.POINTER(C.c_int32)),
+                ("gx_bits", C.c_int32), ("gw_bits", C.c_int32), ("rounding", C.c_int32),
+                ("lqs_threshold", C.c_float)]
+
+
+class HotError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (hot_status {status})")
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """Loads libhot.so; fails loudly if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2503_21261_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        l = C.CDLL(LIB_PATH)
+        i64, vp, sz = C.c_int64, C.c_void_p, C.c_size_t
+        cfgp = C.POINTER(hot_config)
+        l.hot_default_config.argtypes = [cfgp]
+        l.hot_default_config.restype = None
+        l.hot_status_string.argtypes = [C.c_int]
+        l.hot_status_string.restype = C.c_char_p
+        l.hot_act_buffer_bytes.argtypes = [cfgp, i64, i64]
+        l.hot_act_buffer_bytes.restype = sz
+        l.hot_workspace_bytes.argtypes = [cfgp, i64, i64, i64]
+        l.hot_workspace_bytes.restype = sz
+        l.hot_compress_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, sz, vp]
+        l.hot_linear_backward_gx.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+        l.hot_linear_backward_gw.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, sz, vp]
+        l.hot_select_quantizer.argtypes = [cfgp, vp, i64, i64, C.POINTER(C.c_int),
+                                           C.POINTER(C.c_double), C.POINTER(C.c_double), vp, sz, vp]
+        l.hot_debug_unpack_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
+        l.hot_debug_gx_operands.argtypes = [cfgp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp, vp]
+        l.hot_debug_gw_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        for name in EXPORTS[4:]:
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().hot_status_string(int(status)).decode()
+
+
+@dataclass
+class Config:
+    """Python mirror of ``hot_config`` (paper defaults: n=16, r=8, INT4/INT8, PSR, 0.5)."""
+    block: int = 16
+    keep: int = 8
+    keep_idx: Optional[Sequence[int]] = None
+    gx_bits: int = 4
+    gw_bits: int = 8
+    rounding: int = HOT_ROUND_PSEUDO_STOCHASTIC
+    lqs_threshold: float = 0.5
+
+    def c(self) -> hot_config:
+        cfg = hot_config()
+        cfg.block, cfg.keep = int(self.block), int(self.keep)
+        cfg.gx_bits, cfg.gw_bits = int(self.gx_bits), int(self.gw_bits)
+        cfg.rounding, cfg.lqs_threshold = int(self.rounding), float(self.lqs_threshold)
+        if self.keep_idx is None:
+            cfg.keep_idx = None
+            self._keep_arr = None
+        else:
+            self._keep_arr = (C.c_int32 * len(self.keep_idx))(*[int(k) for k in self.keep_idx])
+            cfg.keep_idx = C.cast(self._keep_arr, C.POINTER(C.c_int32))
+        return cfg
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != HOT_OK:
+        raise HotError(status, where)
+
+
+def _dev_f32(t: torch.Tensor, shape: Tuple[int, ...], name: str) -> None:
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
+        raise ValueError(f"{name}: expected contiguous float32 device tensor of shape {shape}")
+
+
+def hot_act_buffer_bytes(cfg: Config, L: int, I: int) -> int:
+    return int(lib().hot_act_buffer_bytes(C.byref(cfg.c()), L, I))
+
+
+def hot_workspace_bytes(cfg: Config, L: int, O: int, I: int) -> int:
+    return int(lib().hot_workspace_bytes(C.byref(cfg.c()), L, O, I))
+
+
+def alloc_workspace(cfg: Config, L: int, O: int, I: int, device="cuda") -> torch.Tensor:
+    n = hot_workspace_bytes(cfg, L, O, I)
+    if n == 0:
+        raise HotError(HOT_ERR_SHAPE, "hot_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def alloc_act_buffer(cfg: Config, L: int, I: int, device="cuda") -> torch.Tensor:
+    n = hot_act_buffer_bytes(cfg, L, I)
+    if n == 0:
+        raise HotError(HOT_ERR_SHAPE, "hot_act_buffer_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def hot_compress_activation(cfg: Config, x: torch.Tensor, act_buf: torch.Tensor,
+                            ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    L, I = x.shape
+    _dev_f32(x, (L, I), "x")
+    st = lib().hot_compress_activation(C.byref(cfg.c()), _ptr(x), L, I, _ptr(act_buf), _ptr(ws),
+                                       0 if ws is None else ws.numel(), _stream(stream))
+    _check(st, "hot_compress_activation")
+    return act_buf
+
+
+def hot_linear_backward_gx(cfg: Config, g_y: torch.Tensor, w: torch.Tensor, gy_quantizer: int,
+                           g_x: torch.Tensor, ws: torch.Tensor, stream=None) -> torch.Tensor:
+    L, O = g_y.shape
+    I = w.shape[1]
+    _dev_f32(g_y, (L, O), "g_y"); _dev_f32(w, (O, I), "w"); _dev_f32(g_x, (L, I), "g_x")
+    st = lib().hot_linear_backward_gx(C.byref(cfg.c()), _ptr(g_y), _ptr(w), L, O, I,
+                                      int(gy_quantizer), _ptr(g_x), _ptr(ws), ws.numel(),
+                                      _stream(stream))
+    _check(st, "hot_linear_backward_gx")
+    return g_x
+
+
+def hot_linear_backward_gw(cfg: Config, g_y: torch.Tensor, act_buf: torch.Tensor, I: int,
+                           g_w: torch.Tensor, ws: torch.Tensor, stream=None) -> torch.Tensor:
+    L, O = g_y.shape
+    _dev_f32(g_y, (L, O), "g_y"); _dev_f32(g_w, (O, I), "g_w")
+    st = lib().hot_linear_backward_gw(C.byref(cfg.c()), _ptr(g_y), _ptr(act_buf), L, O, I,
+                                      _ptr(g_w), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "hot_linear_backward_gw")
+    return g_w
+
+
+def hot_select_quantizer(cfg: Config, g_y: torch.Tensor, ws: torch.Tensor,
+                         stream=None) -> Tuple[int, float, float]:
+    """Returns (choice, mse_token, mse_tensor)."""
+    L, O = g_y.shape
+    _dev_f32(g_y, (L, O), "g_y")
+    choice, mt, mn = C.c_int(-1), C.c_double(0), C.c_double(0)
+    st = lib().hot_select_quantizer(C.byref(cfg.c()), _ptr(g_y), L, O, C.byref(choice),
+                                    C.byref(mt), C.byref(mn), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "hot_select_quantizer")
+    return choice.value, mt.value, mn.value
+
+
+def hot_debug_unpack_activation(cfg: Config, act_buf: torch.Tensor, L: int, I: int, stream=None):
+    """Returns (codes int8 [L*r/n, I], scale float32 [1]) on the device."""
+    Lr = L // cfg.block * cfg.keep
+    codes = torch.empty((Lr, I), dtype=torch.int8, device=act_buf.device)
+    scale = torch.empty(1, dtype=torch.float32, device=act_buf.device)
+    st = lib().hot_debug_unpack_activation(C.byref(cfg.c()), _ptr(act_buf), L, I, _ptr(codes),
+                                           _ptr(scale), _stream(stream))
+    _check(st, "hot_debug_unpack_activation")
+    return codes, scale
+
+
+def hot_debug_gx_operands(cfg: Config, ws: torch.Tensor, L: int, O: int, I: int, gy_quantizer: int,
+                          want_acc: bool = True, stream=None):
+    """Returns dict(qg [L,O] int8, sg [L]|[1], qw [O,I] int8, sw [1], acc [L,I] int32)."""
+    dev = ws.device
+    qg = torch.empty((L, O), dtype=torch.int8, device=dev)
+    sg = torch.empty(L if gy_quantizer == HOT_Q_PER_TOKEN else 1, dtype=torch.float32, device=dev)
+    qw = torch.empty((O, I), dtype=torch.int8, device=dev)
+    sw = torch.empty(1, dtype=torch.float32, device=dev)
+    acc = torch.empty((L, I), dtype=torch.int32, device=dev) if want_acc else None
+    st = lib().hot_debug_gx_operands(C.byref(cfg.c()), _ptr(ws), L, O, I, int(gy_quantizer),
+                                     _ptr(qg), _ptr(sg), _ptr(qw), _ptr(sw), _ptr(acc),
+                                     _stream(stream))
+    _check(st, "hot_debug_gx_operands")
+    return dict(qg=qg, sg=sg, qw=qw, sw=sw, acc=acc)
+
+
+def hot_debug_gw_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, L: int, O: int,
+                          I: int, want_acc: bool = True, stream=None):
+    """Returns dict(qg [L*r/n,O] int8, sg [1], acc [O,I] int32)."""
+    dev = ws.device
+    Lr = L // cfg.block * cfg.keep
+    qg = torch.empty((Lr, O), dtype=torch.int8, device=dev)
+    sg = torch.empty(1, dtype=torch.float32, device=dev)
+    acc = torch.empty((O, I), dtype=torch.int32, device=dev) if want_acc else None
+    st = lib().hot_debug_gw_operands(C.byref(cfg.c()), _ptr(ws), _ptr(act_buf), L, O, I, _ptr(qg),
+                                     _ptr(sg), _ptr(acc), _stream(stream))
+    _check(st, "hot_debug_gw_operands")
+    return dict(qg=qg, sg=sg, acc=acc)

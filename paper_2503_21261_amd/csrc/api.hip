@@ -1,0 +1,354 @@
+// C ABI of libhot: argument checks, workspace layouts and the sequence of
+// kernel launches behind each call declared in hot.h.  No device memory is
+// allocated here; everything lives in caller-provided buffers.
+#include <string.h>
+
+#include "hot_host.h"
+
+namespace hot {
+
+namespace {
+
+// Sign changes along row k of the +-1 Sylvester matrix, entry (k, j) = (-1)^popcount(k & j).
+int row_sign_changes(int n, int k) {
+  int changes = 0, prev = 0;
+  for (int j = 0; j < n; ++j) {
+    const int neg = __builtin_popcount((unsigned)(k & j)) & 1;
+    if (j > 0 && neg != prev) ++changes;
+    prev = neg;
+  }
+  return changes;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+hot_status resolve_config(const hot_config* cfg, Config* out) {
+  if (!cfg || !out) return HOT_ERR_ARG;
+  const int n = cfg->block, r = cfg->keep;
+  if (n != 16 && n != 32 && n != 64) return HOT_ERR_ARG;
+  if (r < 1 || r > n) return HOT_ERR_ARG;
+  if (cfg->gx_bits != 4 && cfg->gx_bits != 8) return HOT_ERR_ARG;
+  if (cfg->gw_bits != 8) return HOT_ERR_ARG;
+  if (cfg->rounding != HOT_ROUND_NEAREST_EVEN && cfg->rounding != HOT_ROUND_PSEUDO_STOCHASTIC)
+    return HOT_ERR_ARG;
+  if (!(cfg->lqs_threshold >= 0.0f)) return HOT_ERR_ARG;
+  out->n = n;
+  out->r = r;
+  out->gx_bits = cfg->gx_bits;
+  out->gw_bits = cfg->gw_bits;
+  out->rounding = cfg->rounding;
+  out->lqs_threshold = cfg->lqs_threshold;
+  out->lowpass_default = cfg->keep_idx == nullptr;
+  for (int k = 0; k < 64; ++k) out->map.pos[k] = -1;
+  for (int j = 0; j < r; ++j) {
+    int k;
+    if (cfg->keep_idx) {
+      k = cfg->keep_idx[j];
+      if (k < 0 || k >= n || out->map.pos[k] >= 0) return HOT_ERR_ARG;
+    } else {
+      // the row with exactly j sign changes (sequencies 0..n-1 each occur once)
+      k = 0;
+      while (k < n && row_sign_changes(n, k) != j) ++k;
+    }
+    out->keep[j] = k;
+    out->map.pos[k] = (int8_t)j;
+  }
+  return HOT_OK;
+}
+
+GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
+  GxLayout g;
+  g.pitch = round_up(O * c.gx_bits / 8, kPitchAlign);
+  g.scalars = 0;
+  g.sg = kHeaderBytes;
+  g.qg = g.sg + (size_t)round_up(L * 4, 256);
+  g.qw = g.qg + (size_t)(L * g.pitch);
+  g.total = g.qw + (size_t)(I * g.pitch);
+  return g;
+}
+
+GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
+  GwLayout g;
+  g.Lr = L / c.n * c.r;
+  g.pitch = round_up(g.Lr, kPitchAlign);
+  g.split_k = gemm_split_k(O, I, g.pitch);
+  g.scalars = 0;
+  g.qg = kHeaderBytes;
+  g.partial = g.qg + (size_t)round_up(O * g.pitch, 256);
+  g.total = g.partial + (g.split_k > 1 ? (size_t)g.split_k * O * I * 4 : 0);
+  return g;
+}
+
+SelLayout sel_layout(const Config&, int64_t L, int64_t) {
+  SelLayout s;
+  s.scalars = 0;
+  s.rowmax = kHeaderBytes;
+  s.partial = s.rowmax + (size_t)round_up(L * 4, 256);
+  s.total = s.partial + (size_t)L * 16;
+  return s;
+}
+
+ActLayout act_layout(const Config& c, int64_t L, int64_t I) {
+  ActLayout a;
+  a.Lr = L / c.n * c.r;
+  a.pitch = round_up(a.Lr, kPitchAlign);
+  a.codes = kHeaderBytes;
+  a.total = a.codes + (size_t)(I * a.pitch);
+  return a;
+}
+
+namespace {
+
+bool gx_shape_ok(const Config& c, int64_t L, int64_t O, int64_t I) {
+  return L >= 1 && I >= 1 && O >= c.n && O % c.n == 0 && L < (1ll << 31) && I < (1ll << 31) &&
+         O <= (c.gx_bits == 4 ? kMaxK4 : kMaxK8);
+}
+bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
+  return cols >= 1 && L >= c.n && L % c.n == 0 && L / c.n * c.r <= kMaxK8 && cols < (1ll << 31);
+}
+
+KeepMap identity_map(int n) {
+  KeepMap m;
+  for (int k = 0; k < 64; ++k) m.pos[k] = k < n ? (int8_t)k : (int8_t)-1;
+  return m;
+}
+
+#define HOT_TRY(expr)                         \
+  do {                                        \
+    if ((expr) != hipSuccess) return HOT_ERR_DEVICE; \
+  } while (0)
+
+}  // namespace
+}  // namespace hot
+
+using namespace hot;
+
+extern "C" {
+
+void hot_default_config(hot_config* cfg) {
+  if (!cfg) return;
+  cfg->block = 16;
+  cfg->keep = 8;
+  cfg->keep_idx = nullptr;
+  cfg->gx_bits = 4;
+  cfg->gw_bits = 8;
+  cfg->rounding = HOT_ROUND_PSEUDO_STOCHASTIC;
+  cfg->lqs_threshold = 0.5f;
+}
+
+const char* hot_status_string(hot_status s) {
+  switch (s) {
+    case HOT_OK: return "ok";
+    case HOT_ERR_ARG: return "invalid argument";
+    case HOT_ERR_SHAPE: return "unsupported shape";
+    case HOT_ERR_WORKSPACE: return "workspace too small";
+    case HOT_ERR_DEVICE: return "HIP runtime error";
+    case HOT_ERR_UNIMPLEMENTED: return "not implemented";
+  }
+  return "unknown status";
+}
+
+size_t hot_act_buffer_bytes(const hot_config* cfg, int64_t L, int64_t I) {
+  Config c;
+  if (resolve_config(cfg, &c) != HOT_OK || !tok_shape_ok(c, L, I)) return 0;
+  return act_layout(c, L, I).total;
+}
+
+size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t I) {
+  Config c;
+  if (resolve_config(cfg, &c) != HOT_OK) return 0;
+  if (L < 1 || O < 1 || I < 1) return 0;
+  size_t need = kHeaderBytes;
+  if (gx_shape_ok(c, L, O, I)) {
+    const size_t a = gx_layout(c, L, O, I).total, b = sel_layout(c, L, O).total;
+    need = a > need ? a : need;
+    need = b > need ? b : need;
+  }
+  if (tok_shape_ok(c, L, O) && tok_shape_ok(c, L, I)) {
+    const size_t a = gw_layout(c, L, O, I).total;
+    need = a > need ? a : need;
+  }
+  return need;
+}
+
+hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_t L, int64_t I,
+                                   void* act_buf, void* /*ws*/, size_t /*ws_bytes*/, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!x || !act_buf || !aligned16(x) || !aligned16(act_buf)) return HOT_ERR_ARG;
+  if (!tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  const ActLayout a = act_layout(c, L, I);
+  uint8_t* base = (uint8_t*)act_buf;
+  float* scale = (float*)base;
+  unsigned* amax = (unsigned*)base + 1;
+  HOT_TRY(launch_fill_u32((unsigned*)base, kHeaderBytes / 4, 0u, s));
+  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 1, nullptr, a.pitch, scale, amax, s));
+  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 2, base + a.codes, a.pitch, scale, amax, s));
+  return HOT_OK;
+}
+
+hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const float* w,
+                                  int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
+                                  float* g_x, void* ws, size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !w || !g_x || !ws || !aligned16(g_y) || !aligned16(w) || !aligned16(g_x) || !aligned16(ws))
+    return HOT_ERR_ARG;
+  if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
+  const GxLayout g = gx_layout(c, L, O, I);
+  if (ws_bytes < g.total) return HOT_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)ws;
+  float* s_w = (float*)(base + g.scalars);
+  unsigned* amax_w = (unsigned*)(base + g.scalars) + 1;
+  unsigned* amax_g = (unsigned*)(base + g.scalars) + 2;
+  float* s_g = (float*)(base + g.sg);
+  uint8_t* qg = base + g.qg;
+  uint8_t* qw = base + g.qw;
+  const KeepMap ident = identity_map(c.n);
+
+  HOT_TRY(launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
+  // H.w along O, one scale, written as [I x O] code rows
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 1, nullptr, g.pitch, s_w, amax_w, s));
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 2, qw, g.pitch, s_w, amax_w, s));
+  // g_y.H^T along O
+  if (gy_quantizer == HOT_Q_PER_TOKEN) {
+    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, amax_g, s));
+  } else {
+    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, amax_g, s));
+    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, amax_g, s));
+  }
+  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, nullptr, g_x, s_g,
+                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s));
+  return HOT_OK;
+}
+
+hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
+                                  int64_t L, int64_t O, int64_t I, float* g_w, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !act_buf || !g_w || !ws || !aligned16(g_y) || !aligned16(act_buf) || !aligned16(g_w) ||
+      !aligned16(ws))
+    return HOT_ERR_ARG;
+  if (!tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  const GwLayout g = gw_layout(c, L, O, I);
+  if (ws_bytes < g.total) return HOT_ERR_WORKSPACE;
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)ws;
+  float* s_g = (float*)(base + g.scalars);
+  unsigned* amax_g = (unsigned*)(base + g.scalars) + 1;
+  uint8_t* qg = base + g.qg;
+  int32_t* partial = g.split_k > 1 ? (int32_t*)(base + g.partial) : nullptr;
+  const uint8_t* abase = (const uint8_t*)act_buf;
+
+  HOT_TRY(launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
+  // HLA(g_y) along L, one scale, written as [O x L'] code rows
+  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 1, nullptr, g.pitch, s_g, amax_g, s));
+  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 2, qg, g.pitch, s_g, amax_g, s));
+  HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.split_k, partial,
+                       nullptr, g_w, s_g, 0, (const float*)abase, c.n, s));
+  return HOT_OK;
+}
+
+hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t L, int64_t O,
+                                hot_quantizer* choice, double* mse_token, double* mse_tensor,
+                                void* ws, size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !choice || !ws || !aligned16(g_y) || !aligned16(ws)) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, 1)) return HOT_ERR_SHAPE;
+  const SelLayout l = sel_layout(c, L, O);
+  if (ws_bytes < l.total) return HOT_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)ws;
+  unsigned* amax = (unsigned*)(base + l.scalars) + 1;
+  double* result = (double*)(base + l.scalars + 64);
+  float* rowmax = (float*)(base + l.rowmax);
+  double* partial = (double*)(base + l.partial);
+
+  HOT_TRY(launch_fill_u32((unsigned*)(base + l.scalars), kHeaderBytes / 4, 0u, s));
+  HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 3, nullptr, 0, rowmax, amax, s));
+  HOT_TRY(launch_quant_error(g_y, L, O, c.n, c.gx_bits, c.rounding, rowmax, amax, partial, result, s));
+  double host[2] = {0.0, 0.0};
+  HOT_TRY(hipMemcpyAsync(host, result, sizeof(host), hipMemcpyDeviceToHost, s));
+  HOT_TRY(hipStreamSynchronize(s));
+  // errors were summed on the rotated tensor; H_u / sqrt(n) is orthonormal, hence the 1/n
+  const double denom = (double)c.n * (double)L * (double)O;
+  const double m_tok = host[0] / denom, m_ten = host[1] / denom;
+  if (mse_token) *mse_token = m_tok;
+  if (mse_tensor) *mse_tensor = m_ten;
+  *choice = (m_ten > 0.0 && (m_ten - m_tok) >= (double)c.lqs_threshold * m_ten) ? HOT_Q_PER_TOKEN
+                                                                               : HOT_Q_PER_TENSOR;
+  return HOT_OK;
+}
+
+hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_buf, int64_t L,
+                                       int64_t I, int8_t* codes, float* scale, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!act_buf) return HOT_ERR_ARG;
+  if (!tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  const uint8_t* base = (const uint8_t*)act_buf;
+  if (codes) HOT_TRY(launch_unpack(base + a.codes, I, a.Lr, a.pitch, 8, 1, codes, s));
+  if (scale) HOT_TRY(hipMemcpyAsync(scale, base, 4, hipMemcpyDeviceToDevice, s));
+  return HOT_OK;
+}
+
+hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t L, int64_t O,
+                                 int64_t I, hot_quantizer gy_quantizer, int8_t* gy_codes,
+                                 float* gy_scales, int8_t* w_codes, float* w_scale, int32_t* acc,
+                                 void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!ws) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
+  const GxLayout g = gx_layout(c, L, O, I);
+  hipStream_t s = (hipStream_t)stream;
+  const uint8_t* base = (const uint8_t*)ws;
+  if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, L, O, g.pitch, c.gx_bits, 0, gy_codes, s));
+  if (w_codes) HOT_TRY(launch_unpack(base + g.qw, I, O, g.pitch, c.gx_bits, 1, w_codes, s));
+  if (gy_scales)
+    HOT_TRY(hipMemcpyAsync(gy_scales, base + g.sg, gy_quantizer == HOT_Q_PER_TOKEN ? L * 4 : 4,
+                           hipMemcpyDeviceToDevice, s));
+  if (w_scale) HOT_TRY(hipMemcpyAsync(w_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
+  if (acc)
+    HOT_TRY(launch_igemm(base + g.qg, base + g.qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, acc,
+                         nullptr, nullptr, 0, nullptr, c.n, s));
+  return HOT_OK;
+}
+
+hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+                                 int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
+                                 float* gy_scale, int32_t* acc, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!ws || (acc && !act_buf)) return HOT_ERR_ARG;
+  if (!tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  const GwLayout g = gw_layout(c, L, O, I);
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  const uint8_t* base = (const uint8_t*)ws;
+  if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, 8, 1, gy_codes, s));
+  if (gy_scale) HOT_TRY(hipMemcpyAsync(gy_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
+  if (acc)
+    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch, 8, 1,
+                         nullptr, acc, nullptr, nullptr, 0, nullptr, c.n, s));
+  return HOT_OK;
+}
+
+}  // extern "C"

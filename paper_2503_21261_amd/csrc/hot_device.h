@@ -1,0 +1,118 @@
+// Device-side helpers shared by the HOT kernels (gfx950 only, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hot {
+
+constexpr int kWave = 64;
+
+// ---- cross-lane exchange: value held by lane (id ^ MASK) -------------------
+// MASK 1, 2 use DPP quad permutes, 4..16 the ds_swizzle bit mode (no LDS memory
+// is touched), 32 swaps the wave halves.
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+  int x = __float_as_int(v);
+  int r;
+  if constexpr (MASK == 1) {
+    r = __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+  } else if constexpr (MASK == 2) {
+    r = __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+  } else if constexpr (MASK == 4 || MASK == 8 || MASK == 16) {
+    r = __builtin_amdgcn_ds_swizzle(x, (MASK << 10) | 0x1F); // and 0x1F, or 0, xor MASK
+  } else {
+    static_assert(MASK == 32, "lane_xor mask");
+    r = __builtin_amdgcn_ds_bpermute(((int)(threadIdx.x & 63) ^ 32) << 2, x);
+  }
+  return __int_as_float(r);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, lane_xor<1>(v));
+  v = fmaxf(v, lane_xor<2>(v));
+  v = fmaxf(v, lane_xor<4>(v));
+  v = fmaxf(v, lane_xor<8>(v));
+  v = fmaxf(v, lane_xor<16>(v));
+  v = fmaxf(v, lane_xor<32>(v));
+  return v;
+}
+
+// One butterfly stage across lanes: the lane whose MASK bit is clear holds the
+// lower element a, its partner the upper element b; (a, b) -> (a + b, a - b).
+template <int MASK>
+__device__ __forceinline__ float butterfly_lanes(float v, bool upper) {
+  float p = lane_xor<MASK>(v);
+  return upper ? (p - v) : (v + p);
+}
+
+// In-register Walsh-Hadamard butterflies of a length-N array (Sec. 3.1), stages
+// h = 1, 2, 4, ... in that order: element j with bit h clear pairs with j + h.
+template <int N>
+__device__ __forceinline__ void fwht_regs(float (&v)[N]) {
+#pragma unroll
+  for (int h = 1; h < N; h *= 2) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      if ((j & h) == 0) {
+        float a = v[j], b = v[j + h];
+        v[j] = a + b;
+        v[j + h] = a - b;
+      }
+    }
+  }
+}
+
+// Stages h = 1 .. N/2 of the transform for the 4 elements this lane holds;
+// `lane` is the lane's index within the row (its low bits select the block half).
+template <int N>
+__device__ __forceinline__ void fwht_row4(float4& q, int lane) {
+  float x = q.x + q.y, y = q.x - q.y, z = q.z + q.w, w = q.z - q.w;  // h = 1
+  q.x = x + z; q.z = x - z; q.y = y + w; q.w = y - w;                // h = 2
+#define HOT_STAGE(MASK)                                      \
+  {                                                          \
+    const bool up = (lane & MASK) != 0;                      \
+    q.x = butterfly_lanes<MASK>(q.x, up);                    \
+    q.y = butterfly_lanes<MASK>(q.y, up);                    \
+    q.z = butterfly_lanes<MASK>(q.z, up);                    \
+    q.w = butterfly_lanes<MASK>(q.w, up);                    \
+  }
+  HOT_STAGE(1)  // h = 4
+  HOT_STAGE(2)  // h = 8
+  if constexpr (N >= 32) HOT_STAGE(4)   // h = 16
+  if constexpr (N >= 64) HOT_STAGE(8)   // h = 32
+#undef HOT_STAGE
+}
+
+__device__ __forceinline__ float absmax4(const float4& q) {
+  return fmaxf(fmaxf(fabsf(q.x), fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w)));
+}
+
+// ---- quantiser (Sec. 5.1) ---------------------------------------------------
+// scale = amax / qmax, inv = qmax / amax (IEEE fp32 divisions), 0 for a zero group.
+__device__ __forceinline__ float quant_scale(float amax, int qmax) { return amax / (float)qmax; }
+__device__ __forceinline__ float quant_inv(float amax, int qmax) {
+  return amax > 0.0f ? (float)qmax / amax : 0.0f;
+}
+
+// code = clamp(round(t * inv)); pseudo-stochastic rounding compares the fractional
+// part with the low 11 bits of the scaled value's own fp32 pattern, as a fraction.
+__device__ __forceinline__ int quant_code(float t, float inv, int qmax, int rounding) {
+  float v = t * inv;
+  int q;
+  if (rounding == 0) {
+    q = (int)rintf(v);
+  } else {
+    float f = floorf(v);
+    float frac = v - f;
+    float rnd = (float)(__float_as_uint(v) & 0x7FFu) * (1.0f / 2048.0f);
+    q = (int)f + (frac > rnd ? 1 : 0);
+  }
+  return min(max(q, -qmax), qmax);
+}
+
+// Non-negative floats order like their bit patterns: abs-max via integer atomicMax.
+__device__ __forceinline__ void atomic_absmax(unsigned* slot, float amax) {
+  atomicMax(slot, __float_as_uint(amax));
+}
+
+}  // namespace hot

@@ -1,0 +1,109 @@
+// Host-side declarations shared by the translation units of libhot: argument
+// checks, workspace layouts and the launchers each .hip file defines.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "hot.h"
+
+namespace hot {
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Position of every natural-order row of an n-block in the kept list (-1 = dropped).
+struct KeepMap {
+  int8_t pos[64];
+};
+
+// Validated, resolved form of hot_config.
+struct Config {
+  int n, r, gx_bits, gw_bits, rounding;
+  float lqs_threshold;
+  int keep[64];   // r natural-order indices, in output order
+  KeepMap map;    // inverse of keep
+  bool lowpass_default;
+};
+
+hot_status resolve_config(const hot_config* cfg, Config* out);
+
+// K-contiguous operand rows are padded with zero codes to a multiple of 128 bytes.
+constexpr int64_t kPitchAlign = 128;
+constexpr int64_t kHeaderBytes = 256;
+// |code products| summed over K must fit int32 (INT4 operands are fed to the
+// matrix cores as 16 x code, so their bound carries a factor 256).
+constexpr int64_t kMaxK8 = 133144;   // 127^2 * K < 2^31
+constexpr int64_t kMaxK4 = 171196;   // 256 * 7^2 * K < 2^31
+
+struct GxLayout {
+  int64_t pitch;                      // bytes per operand row (K = O codes)
+  size_t scalars, sg, qg, qw, total;  // byte offsets into ws
+};
+struct GwLayout {
+  int64_t Lr, pitch;                  // reduced token count, bytes per operand row
+  int split_k;
+  size_t scalars, qg, partial, total;
+};
+struct SelLayout {
+  size_t scalars, rowmax, partial, total;
+};
+struct ActLayout {
+  int64_t Lr, pitch;
+  size_t codes, total;
+};
+
+GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I);
+GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I);
+SelLayout sel_layout(const Config& c, int64_t L, int64_t O);
+ActLayout act_layout(const Config& c, int64_t L, int64_t I);
+int gemm_split_k(int64_t M, int64_t N, int64_t k_bytes);
+
+// ---- launchers (each returns hipGetLastError() of its launches) -------------
+
+// Row-direction block WHT + quantise of t [rows x cols] (cols % n == 0).
+//   mode 0: per-token: codes + scales[rows].
+//   mode 1: abs-max of the rotated tensor into *amax_bits (atomic max, must be
+//           zeroed first); nothing else is written.
+//   mode 2: quantise with the tensor-wide abs-max in *amax_bits; scales[0] written.
+//   mode 3: abs-max per row into scales[rows] and tensor-wide into *amax_bits.
+// codes: rows x pitch bytes, `bits` = 4 (two codes per byte, even index in the
+// low nibble) or 8; bytes from cols*bits/8 up to pitch are zero-filled.
+hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, int bits,
+                            int rounding, int mode, uint8_t* codes, int64_t pitch, float* scales,
+                            unsigned* amax_bits, hipStream_t s);
+
+// Column-direction block WHT (blocks of n consecutive rows of x [R x C]), keep r
+// rows per block, one scale for the tensor; output transposed: row c of `codes`
+// holds the kept values of column c, reduced row index contiguous.
+//   mode 1: abs-max of the kept rotated values into *amax_bits (atomic max).
+//   mode 2: quantise with *amax_bits; *scale written; pad bytes zero-filled.
+hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& cfg, int r,
+                            const KeepMap& map, int bits, int mode, uint8_t* codes,
+                            int64_t pitch, float* scale, unsigned* amax_bits, hipStream_t s);
+
+hipError_t launch_fill_u32(unsigned* p, int64_t count, unsigned value, hipStream_t s);
+
+// C[M x N] = A[M x K] . B[N x K]^T on K-contiguous code rows (pitch bytes each,
+// k_bytes = K * bits / 8 rounded up to the pitch alignment).
+//   out_i32 != NULL: raw int32 accumulators, row-major [M x N].
+//   out_f32 != NULL: out = acc * row_scale[m * row_stride] * (*col_scale) / n.
+// split_k > 1 accumulates K-slices in `partial` ([split_k x M x N] int32) first.
+hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
+                        int64_t pitch, int bits, int split_k, int32_t* partial, int32_t* out_i32,
+                        float* out_f32, const float* row_scale, int row_stride,
+                        const float* col_scale, int n, hipStream_t s);
+
+// Unpack K-contiguous codes [rows x pitch] into one int8 per code.
+//   transpose = 0: out[row * K + k];  transpose = 1: out[k * rows + row].
+hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t pitch, int bits,
+                         int transpose, int8_t* out, hipStream_t s);
+
+// Squared quantisation error of the rotated t [rows x cols] with per-token and
+// per-tensor scales (rowmax[rows], *amax_bits from launch_row_quant mode 3):
+// result[0] = sum per-token, result[1] = sum per-tensor (double, fixed order).
+hipError_t launch_quant_error(const float* t, int64_t rows, int64_t cols, int n, int bits,
+                              int rounding, const float* rowmax, const unsigned* amax_bits,
+                              double* partial, double* result, hipStream_t s);
+
+}  // namespace hot

@@ -1,0 +1,219 @@
+// Row-direction block Walsh-Hadamard transform fused with abs-max and
+// quantisation: the g_y operand of the g_x path (Sec. 5.1) and the first half of
+// quantizer selection (Sec. 5.2.2).
+//
+// Each row is read once with fully coalesced 16-byte loads and kept in
+// registers.  A lane holds 4 consecutive elements, so butterfly stages h = 1, 2
+// are in-lane and stages h = 4 .. n/2 exchange with lanes id^1, id^2, id^4, id^8
+// (DPP / ds_swizzle).  HBM-bound: 4 bytes read and bits/8 bytes written per
+// element.
+#include "hot_device.h"
+#include "hot_host.h"
+
+namespace hot {
+
+__device__ __forceinline__ void store_codes4(uint8_t* row_codes, int e, const float4& q, float inv,
+                                             int qmax, int bits, int rounding) {
+  const int c0 = quant_code(q.x, inv, qmax, rounding), c1 = quant_code(q.y, inv, qmax, rounding);
+  const int c2 = quant_code(q.z, inv, qmax, rounding), c3 = quant_code(q.w, inv, qmax, rounding);
+  if (bits == 4) {
+    const unsigned p = (c0 & 0xF) | ((c1 & 0xF) << 4) | ((c2 & 0xF) << 8) | ((c3 & 0xF) << 12);
+    *reinterpret_cast<uint16_t*>(row_codes + (e >> 1)) = (uint16_t)p;
+  } else {
+    const unsigned p = (c0 & 0xFF) | ((c1 & 0xFF) << 8) | ((c2 & 0xFF) << 16) | ((unsigned)(c3 & 0xFF) << 24);
+    *reinterpret_cast<uint32_t*>(row_codes + e) = p;
+  }
+}
+
+// TPR threads per row (64: one wave per row, 4 rows per workgroup; 256: one row per
+// workgroup), ITER float4 per thread, so a row of up to 4*TPR*ITER elements lives
+// in registers.
+template <int N, int ITER, int TPR>
+__global__ __launch_bounds__(256) void row_quant_kernel(const float* __restrict__ t, int64_t rows,
+                                                        int cols, int bits, int rounding, int mode,
+                                                        uint8_t* __restrict__ codes, int64_t pitch,
+                                                        float* __restrict__ scales,
+                                                        unsigned* __restrict__ amax_bits) {
+  constexpr int RPB = 256 / TPR;
+  __shared__ float s_max[4];
+  const int tid = threadIdx.x;
+  const int rl = tid / TPR, tr = tid % TPR;
+  const int qmax = (1 << (bits - 1)) - 1;
+  const int64_t nrb = (rows + RPB - 1) / RPB;
+  const int valid_bytes = cols * bits / 8;
+  float running = 0.0f;  // modes 1, 3: abs-max over all rows this thread's group saw
+
+  for (int64_t rb = blockIdx.x; rb < nrb; rb += gridDim.x) {
+    const int64_t row = rb * RPB + rl;
+    const bool row_ok = row < rows;
+    const float4* src = reinterpret_cast<const float4*>(t + row * (int64_t)cols);
+    float4 v[ITER];
+    float m = 0.0f;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int e = (it * TPR + tr) * 4;
+      v[it] = (row_ok && e < cols) ? src[it * TPR + tr] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      fwht_row4<N>(v[it], tr);
+      m = fmaxf(m, absmax4(v[it]));
+    }
+    float amax;
+    if (mode == 2) {
+      amax = __uint_as_float(*amax_bits);
+    } else {
+      m = wave_max(m);
+      if constexpr (TPR == 256) {
+        if ((tid & 63) == 0) s_max[tid >> 6] = m;
+        __syncthreads();
+        m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+        __syncthreads();
+      }
+      amax = m;
+    }
+    if (mode == 1 || mode == 3) {
+      running = fmaxf(running, amax);
+      if (mode == 3 && tr == 0 && row_ok) scales[row] = amax;
+      continue;
+    }
+    if (mode == 0 && tr == 0 && row_ok) scales[row] = quant_scale(amax, qmax);
+    const float inv = quant_inv(amax, qmax);
+    if (row_ok) {
+      uint8_t* row_codes = codes + row * pitch;
+#pragma unroll
+      for (int it = 0; it < ITER; ++it) {
+        const int e = (it * TPR + tr) * 4;
+        if (e < cols) store_codes4(row_codes, e, v[it], inv, qmax, bits, rounding);
+      }
+      for (int off = valid_bytes + 4 * tr; off < pitch; off += 4 * TPR)
+        *reinterpret_cast<uint32_t*>(row_codes + off) = 0u;
+    }
+  }
+  if (mode == 1 || mode == 3) {
+    // every lane of a row group holds that group's maximum; one atomic per wave
+    if ((tid & 63) == 0) atomic_absmax(amax_bits, running);
+  } else if (mode == 2 && blockIdx.x == 0 && tid == 0) {
+    scales[0] = quant_scale(__uint_as_float(*amax_bits), qmax);
+  }
+}
+
+// Rows longer than the register-resident variants cover: one row per workgroup,
+// transformed twice (abs-max pass, then quantise pass; the second read hits L2).
+template <int N>
+__global__ __launch_bounds__(256) void row_quant_stream_kernel(
+    const float* __restrict__ t, int64_t rows, int cols, int bits, int rounding, int mode,
+    uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scales,
+    unsigned* __restrict__ amax_bits) {
+  __shared__ float s_max[4];
+  const int tid = threadIdx.x;
+  const int qmax = (1 << (bits - 1)) - 1;
+  const int valid_bytes = cols * bits / 8;
+  const int nvec = cols / 4;
+  float running = 0.0f;
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+    const float4* src = reinterpret_cast<const float4*>(t + row * (int64_t)cols);
+    float amax;
+    if (mode == 2) {
+      amax = __uint_as_float(*amax_bits);
+    } else {
+      float m = 0.0f;
+      for (int base = 0; base < nvec; base += 256) {  // uniform trip count: shuffles stay converged
+        const int i = base + tid;
+        float4 q = i < nvec ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        fwht_row4<N>(q, tid);
+        m = fmaxf(m, absmax4(q));
+      }
+      m = wave_max(m);
+      if ((tid & 63) == 0) s_max[tid >> 6] = m;
+      __syncthreads();
+      amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+      __syncthreads();
+    }
+    if (mode == 1 || mode == 3) {
+      running = fmaxf(running, amax);
+      if (mode == 3 && tid == 0) scales[row] = amax;
+      continue;
+    }
+    if (mode == 0 && tid == 0) scales[row] = quant_scale(amax, qmax);
+    const float inv = quant_inv(amax, qmax);
+    uint8_t* row_codes = codes + row * pitch;
+    for (int base = 0; base < nvec; base += 256) {
+      const int i = base + tid;
+      float4 q = i < nvec ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      fwht_row4<N>(q, tid);
+      if (i < nvec) store_codes4(row_codes, i * 4, q, inv, qmax, bits, rounding);
+    }
+    for (int off = valid_bytes + 4 * tid; off < pitch; off += 4 * 256)
+      *reinterpret_cast<uint32_t*>(row_codes + off) = 0u;
+  }
+  if (mode == 1 || mode == 3) {
+    if (tid == 0) atomic_absmax(amax_bits, running);
+  } else if (mode == 2 && blockIdx.x == 0 && tid == 0) {
+    scales[0] = quant_scale(__uint_as_float(*amax_bits), qmax);
+  }
+}
+
+__global__ void fill_u32_kernel(unsigned* p, int64_t count, unsigned value) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) p[i] = value;
+}
+
+hipError_t launch_fill_u32(unsigned* p, int64_t count, unsigned value, hipStream_t s) {
+  if (count <= 0) return hipSuccess;
+  fill_u32_kernel<<<dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, s>>>(p, count, value);
+  return hipGetLastError();
+}
+
+namespace {
+
+constexpr int kMaxGrid = 2048;  // grid-stride cap: bounds the atomics of the abs-max modes
+
+template <int N>
+hipError_t dispatch_row_quant(const float* t, int64_t rows, int cols, int bits, int rounding,
+                              int mode, uint8_t* codes, int64_t pitch, float* scales,
+                              unsigned* amax_bits, hipStream_t s) {
+#define HOT_LAUNCH(ITER, TPR)                                                                  \
+  {                                                                                            \
+    const int64_t nrb = ceil_div(rows, 256 / TPR);                                             \
+    const unsigned grid = (unsigned)((mode == 1 || mode == 3) ? (nrb < kMaxGrid ? nrb : kMaxGrid) \
+                                                              : (nrb < (1 << 20) ? nrb : (1 << 20))); \
+    row_quant_kernel<N, ITER, TPR><<<dim3(grid), dim3(256), 0, s>>>(                           \
+        t, rows, cols, bits, rounding, mode, codes, pitch, scales, amax_bits);                 \
+    return hipGetLastError();                                                                  \
+  }
+  const int v64 = (int)ceil_div(cols, 256);    // float4 per thread with one wave per row
+  const int v256 = (int)ceil_div(cols, 1024);  // float4 per thread with one workgroup per row
+  if (v64 <= 1) HOT_LAUNCH(1, 64)
+  if (v64 <= 2) HOT_LAUNCH(2, 64)
+  if (v64 <= 3) HOT_LAUNCH(3, 64)
+  if (v64 <= 4) HOT_LAUNCH(4, 64)
+  if (v256 <= 2) HOT_LAUNCH(2, 256)
+  if (v256 <= 3) HOT_LAUNCH(3, 256)
+  if (v256 <= 4) HOT_LAUNCH(4, 256)
+  if (v256 <= 6) HOT_LAUNCH(6, 256)
+  if (v256 <= 8) HOT_LAUNCH(8, 256)
+  if (v256 <= 11) HOT_LAUNCH(11, 256)
+  if (v256 <= 16) HOT_LAUNCH(16, 256)
+#undef HOT_LAUNCH
+  const unsigned grid = (unsigned)(rows < kMaxGrid ? rows : kMaxGrid);
+  row_quant_stream_kernel<N><<<dim3(grid), dim3(256), 0, s>>>(t, rows, cols, bits, rounding, mode,
+                                                              codes, pitch, scales, amax_bits);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, int bits,
+                            int rounding, int mode, uint8_t* codes, int64_t pitch, float* scales,
+                            unsigned* amax_bits, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  switch (n) {
+    case 16: return dispatch_row_quant<16>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
+    case 32: return dispatch_row_quant<32>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
+    case 64: return dispatch_row_quant<64>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace hot

@@ -1,0 +1,256 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element on the same seeded inputs.  Integer stages - codes, scales (fp32 bit
+patterns) and int32 accumulators - must be identical; dequantised fp32 outputs
+must agree within 1e-5 relative in max-norm (fp32 epilogue: one int->float
+conversion and two multiplies, ~2e-7)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import hot_inputs
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-5
+
+
+def _hot():
+    import paper_2503_21261_amd as hot
+    return hot
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def assert_close_maxnorm(got, ref, what):
+    denom = np.max(np.abs(ref))
+    err = np.max(np.abs(got.astype(np.float64) - ref))
+    assert err <= REL_TOL * denom + 1e-300, f"{what}: max err {err:.3e} vs max|ref| {denom:.3e}"
+
+
+def bits_equal(a, b):
+    return np.array_equal(np.asarray(a, np.float32).view(np.uint32), np.asarray(b, np.float32).view(np.uint32))
+
+
+def check_gx(hot, cfg, gy, w, per_token, what):
+    L, O = gy.shape
+    I = w.shape[1]
+    _say(f"[gx] {what} L={L} O={O} I={I} n={cfg.block} bits={cfg.gx_bits} token={per_token} round={cfg.rounding}")
+    ref = oracle.backward_gx(gy.numpy(), w.numpy(), cfg.block, bits=cfg.gx_bits, per_token=per_token,
+                             rounding=cfg.rounding)
+    assert ref["overflow"] == 0
+    gyd, wd = gy.cuda(), w.cuda()
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    gx = torch.empty((L, I), dtype=torch.float32, device="cuda")
+    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
+    hot.hot_linear_backward_gx(cfg, gyd, wd, q, gx, ws)
+    taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q)
+    torch.cuda.synchronize()
+    assert bits_equal(taps["sg"].cpu().numpy(), ref["sg"]), f"{what}: g_y scales differ"
+    assert bits_equal(taps["sw"].cpu().numpy(), ref["sw"]), f"{what}: w scale differs"
+    assert np.array_equal(taps["qg"].cpu().numpy(), ref["qg"]), f"{what}: g_y codes differ"
+    assert np.array_equal(taps["qw"].cpu().numpy(), ref["qw"]), f"{what}: w codes differ"
+    assert np.array_equal(taps["acc"].cpu().numpy().astype(np.int64), ref["acc"]), f"{what}: accumulators differ"
+    assert_close_maxnorm(gx.cpu().numpy(), ref["g_x"], what + " g_x")
+    return ref, gx
+
+
+def check_gw(hot, cfg, gy, x, what):
+    L, O = gy.shape
+    I = x.shape[1]
+    _say(f"[gw] {what} L={L} O={O} I={I} n={cfg.block} r={cfg.keep} keep={cfg.keep_idx} round={cfg.rounding}")
+    keep = None if cfg.keep_idx is None else list(cfg.keep_idx)
+    codes_ref, sx_ref = oracle.compress_activation(x.numpy(), cfg.block, cfg.keep, keep=keep,
+                                                   rounding=cfg.rounding)
+    ref = oracle.backward_gw(gy.numpy(), codes_ref, sx_ref, cfg.block, cfg.keep, keep=keep,
+                             rounding=cfg.rounding)
+    assert ref["overflow"] == 0
+    gyd, xd = gy.cuda(), x.cuda()
+    act = hot.alloc_act_buffer(cfg, L, I)
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    hot.hot_compress_activation(cfg, xd, act)
+    codes, sx = hot.hot_debug_unpack_activation(cfg, act, L, I)
+    gw = torch.empty((O, I), dtype=torch.float32, device="cuda")
+    hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
+    taps = hot.hot_debug_gw_operands(cfg, ws, act, L, O, I)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), [sx_ref]), f"{what}: activation scale differs"
+    assert np.array_equal(codes.cpu().numpy(), codes_ref), f"{what}: activation codes differ"
+    assert bits_equal(taps["sg"].cpu().numpy(), [ref["sg"]]), f"{what}: HLA(g_y) scale differs"
+    assert np.array_equal(taps["qg"].cpu().numpy(), ref["qg"]), f"{what}: HLA(g_y) codes differ"
+    assert np.array_equal(taps["acc"].cpu().numpy().astype(np.int64), ref["acc"]), f"{what}: accumulators differ"
+    assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w")
+    return ref, gw
+
+
+def make(L, O, I, seed, gy_kind="chan_outlier", x_kind="normal"):
+    name = f"t{L}x{O}x{I}"
+    return (hot_inputs.make_x(x_kind, L, I, seed, name), hot_inputs.make_w(O, I, seed, name),
+            hot_inputs.make_gy(gy_kind, L, O, seed, name))
+
+
+# shapes span several 128x128 GEMM tiles, ragged M/N tails, K that is / is not a
+# multiple of the 128-byte operand pitch, and rows that fill 1..many register slots
+GX_SHAPES = [
+    (16, 16, 4),        # one block, one tile
+    (1, 64, 1),         # single token, single input channel
+    (48, 64, 40),
+    (130, 160, 72),     # ragged everywhere
+    (257, 1040, 130),   # row longer than one wave's 4 slots (workgroup-per-row variant)
+    (300, 2304, 200),
+]
+
+
+@pytest.mark.parametrize("n", [16, 32, 64])
+@pytest.mark.parametrize("shape", GX_SHAPES)
+def test_gx_small_shapes_per_token(n, shape):
+    L, O, I = shape
+    if O % n:
+        pytest.skip("O not a multiple of n")
+    hot = _hot()
+    x, w, gy = make(L, O, I, seed=3)
+    check_gx(hot, hot.Config(block=n, keep=n // 2), gy, w, True, "small")
+
+
+@pytest.mark.parametrize("n,bits,rounding", [(16, 4, 0), (16, 8, 1), (32, 8, 0), (64, 4, 1)])
+@pytest.mark.parametrize("per_token", [True, False])
+def test_gx_variants(n, bits, rounding, per_token):
+    hot = _hot()
+    x, w, gy = make(200, 384, 136, seed=5, gy_kind="tok_outlier")
+    cfg = hot.Config(block=n, keep=n // 2, gx_bits=bits, rounding=rounding)
+    check_gx(hot, cfg, gy, w, per_token, "variant")
+
+
+def test_gx_config1_full():
+    """configs[0]: L=512, O=768, I=768, n=16, INT4 per token."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg1_single_512x768x768"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    ref, gx = check_gx(hot, cfg, gy, w, True, "cfg1")
+    check_gx(hot, cfg, gy, w, False, "cfg1 per-tensor")
+    exact, _ = oracle.exact_backward(gy.numpy(), x.numpy(), w.numpy(), want_gw=False)
+    rel = np.linalg.norm(gx.cpu().numpy() - exact) / np.linalg.norm(exact)
+    _say(f"cfg1 g_x relative Frobenius error vs exact backward (statistic): {rel:.4f}")
+
+
+def test_gx_long_rows_register_limit_and_streaming():
+    hot = _hot()
+    for O in (16384, 16448):   # largest register-resident row; first streamed row
+        x, w, gy = make(5, O, 24, seed=7, gy_kind="t4")
+        check_gx(hot, hot.Config(block=64, keep=32), gy, w, True, f"long row O={O}")
+        check_gx(hot, hot.Config(block=16, keep=8), gy, w, False, f"long row O={O}")
+
+
+def test_gx_zero_inputs_give_zero():
+    hot = _hot()
+    cfg = hot.Config()
+    gy = torch.zeros(64, 64)
+    w = hot_inputs.make_w(64, 32, 0, "z")
+    gy[3] = hot_inputs.normal((64,), 1e-3, 0, "zrow")  # one live token among zero tokens
+    ref, gx = check_gx(hot, cfg, gy, w, True, "zero rows")
+    assert not gx.cpu().numpy()[0].any()
+    ref, gx = check_gx(hot, cfg, torch.zeros(64, 64), w, False, "all zero")
+    assert not gx.cpu().numpy().any()
+
+
+GW_CASES = [
+    # L, O, I, n, r, keep_idx
+    (16, 8, 4, 16, 8, None),
+    (64, 40, 24, 16, 8, None),
+    (272, 130, 72, 16, 8, None),     # L' = 136: not a multiple of the operand pitch
+    (512, 200, 136, 32, 16, None),
+    (1024, 96, 260, 64, 32, None),
+    (256, 64, 64, 16, 16, None),     # full rank
+    (256, 64, 64, 16, 1, None),      # rank 1: block means
+    (240, 64, 72, 16, 3, None),      # odd rank
+    (256, 64, 64, 16, 4, [5, 0, 9, 14]),   # caller-supplied rows
+    (2048, 300, 140, 16, 8, None),   # several K stages and split-K slices
+]
+
+
+@pytest.mark.parametrize("case", GW_CASES)
+def test_gw_small_shapes(case):
+    L, O, I, n, r, keep = case
+    hot = _hot()
+    x, w, gy = make(L, O, I, seed=11, gy_kind="t4")
+    check_gw(hot, hot.Config(block=n, keep=r, keep_idx=keep), gy, x, "small")
+
+
+def test_gw_nearest_even_and_bf16_inputs():
+    hot = _hot()
+    x, w, gy = make(512, 96, 80, seed=13, x_kind="bf16")
+    check_gw(hot, hot.Config(block=32, keep=16, rounding=0), gy, x, "rne")
+
+
+def test_gw_config1_full():
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg1_single_512x768x768"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    ref, gw = check_gw(hot, cfg, gy, x, "cfg1")
+    L, I = x.shape
+    assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + L * I // 8  # 12.5 % of fp32 (Sec. 5.2.1)
+    _, exact = oracle.exact_backward(gy.numpy(), x.numpy(), w.numpy(), want_gx=False)
+    rel = np.linalg.norm(gw.cpu().numpy() - exact) / np.linalg.norm(exact)
+    _say(f"cfg1 g_w relative Frobenius error vs exact backward (statistic): {rel:.4f}")
+
+
+@pytest.mark.parametrize("kind,n", [("tok_outlier", 16), ("chan_outlier", 16), ("t3", 64), ("normal", 32)])
+def test_select_quantizer_matches_oracle(kind, n):
+    hot = _hot()
+    L, O = 384, 512
+    gy = hot_inputs.make_gy(kind, L, O, 17, "sel")
+    _say(f"[select] kind={kind} n={n} L={L} O={O}")
+    cfg = hot.Config(block=n, keep=n // 2)
+    ws = hot.alloc_workspace(cfg, L, O, 64)
+    choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, gy.cuda(), ws)
+    ref_choice, r_tok, r_ten = oracle.select_quantizer(gy.numpy(), n, bits=4, rounding=cfg.rounding,
+                                                       threshold=cfg.lqs_threshold)
+    # same codes and scales on both sides; only the order of the double sums differs
+    np.testing.assert_allclose(m_tok, r_tok, rtol=1e-10)
+    np.testing.assert_allclose(m_ten, r_ten, rtol=1e-10)
+    assert choice == int(ref_choice)
+    if kind == "tok_outlier":
+        assert choice == hot.HOT_Q_PER_TOKEN
+    if kind == "normal":
+        assert choice == hot.HOT_Q_PER_TENSOR
+
+
+def test_select_quantizer_zero_gradient():
+    hot = _hot()
+    cfg = hot.Config()
+    ws = hot.alloc_workspace(cfg, 32, 64, 16)
+    choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, torch.zeros(32, 64, device="cuda"), ws)
+    assert (choice, m_tok, m_ten) == (hot.HOT_Q_PER_TENSOR, 0.0, 0.0)
+
+
+def test_calls_are_repeatable_and_stream_ordered():
+    """Same inputs, same workspace, non-default stream: identical bits every time."""
+    hot = _hot()
+    x, w, gy = make(300, 320, 200, seed=19)
+    cfg = hot.Config()
+    L, O = gy.shape
+    I = w.shape[1]
+    gyd, wd, xd = gy.cuda(), w.cuda(), x.cuda()
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    act = hot.alloc_act_buffer(cfg, L, I)
+    outs = []
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        gx = torch.empty((L, I), device="cuda")
+        gw = torch.empty((O, I), device="cuda")
+        with torch.cuda.stream(s):
+            hot.hot_compress_activation(cfg, xd, act, stream=s)
+            hot.hot_linear_backward_gx(cfg, gyd, wd, hot.HOT_Q_PER_TOKEN, gx, ws, stream=s)
+            hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws, stream=s)
+        s.synchronize()
+        outs.append((gx.cpu().numpy().copy(), gw.cpu().numpy().copy()))
+    for gx, gw in outs[1:]:
+        assert np.array_equal(gx, outs[0][0]) and np.array_equal(gw, outs[0][1])
