@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the HOT linear-layer backward hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+forward-time activation compression, the g_x path and the g_w path of one
+linear layer (Sec. 5.1, 5.2, 5.2.1).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA
+
+
+def stage_model(L, O, I, n, r, gx_bits, per_token):
+    """Algorithmic work per launch of every kernel role: HBM bytes for the
+    transform/quantise kernels, integer ops (and compulsory bytes) for the GEMMs."""
+    Lr = L // n * r
+    cb = gx_bits / 8.0
+    m = {
+        "act_col_absmax": dict(bound="hbm", bytes=4 * L * I),
+        "act_col_quant": dict(bound="hbm", bytes=4 * L * I + Lr * I),
+        "w_col_absmax": dict(bound="hbm", bytes=4 * O * I),
+        "w_col_quant": dict(bound="hbm", bytes=4 * O * I + cb * O * I),
+        "gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L),
+        "gy_row_absmax": dict(bound="hbm", bytes=4 * L * O),
+        "gy_row_quant2": dict(bound="hbm", bytes=4 * L * O + cb * L * O),
+        "gyT_col_absmax": dict(bound="hbm", bytes=4 * L * O),
+        "gyT_col_quant": dict(bound="hbm", bytes=4 * L * O + Lr * O),
+        "gx_igemm": dict(bound="mfma", ops=2 * L * O * I, bytes=cb * (L * O + I * O) + 4 * L * I),
+        "gw_igemm": dict(bound="mfma", ops=2 * O * I * Lr, bytes=Lr * (O + I) + 4 * O * I),
+    }
+    return m
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_vitb_fc1")
+    ap.add_argument("--quantizer", default=None, choices=[None, "token", "tensor"])
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs the HOT backward on ONE GPU; "
+                         "--gpus N with N > 1 is not supported.\n")
+        return 2
+
+    import torch
+    import hot_inputs
+    import paper_2503_21261_amd as hot
+
+    hot.lib()  # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    wl = hot_inputs.WORKLOADS[args.workload]
+    layer = wl.layers[0]
+    L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep
+    quant = args.quantizer or ("token" if wl.quantizer in ("token", "select") else "tensor")
+    per_token = quant == "token"
+    cfg = hot.Config(block=n, keep=r)
+
+    x, w, gy = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    act = hot.alloc_act_buffer(cfg, L, I)
+    gx = torch.empty((L, I), device="cuda")
+    gw = torch.empty((O, I), device="cuda")
+    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
+    stream = torch.cuda.current_stream()
+
+    def step():
+        hot.hot_compress_activation(cfg, x, act, stream=stream)
+        hot.hot_linear_backward_gx(cfg, gy, w, q, gx, ws, stream=stream)
+        hot.hot_linear_backward_gw(cfg, gy, act, I, gw, ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # same steps again with HIP events around every kernel (on the launch stream)
+    hot.hot_debug_profile_begin()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = hot.hot_debug_profile_end()
+
+    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token)
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        avg_us = ms * 1e3 / cnt
+        k = dict(avg_us=round(avg_us, 3), launches_per_step=cnt / args.steps)
+        mdl = model.get(name)
+        if mdl:
+            k["bound"] = mdl["bound"]
+            k["GBps"] = round(mdl["bytes"] / (avg_us * 1e-6) / 1e9, 1)
+            if "ops" in mdl:
+                k["TOPS"] = round(mdl["ops"] / (avg_us * 1e-6) / 1e12, 2)
+        kernels[name] = k
+    dominant = max((k for k in kernels if k in model), key=lambda k: kernels[k]["avg_us"])
+    d, dm = kernels[dominant], model[dominant]
+    if dm["bound"] == "hbm":
+        roof = dict(kernel=dominant, bound="hbm", achieved=d["GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(d["GBps"] / HBM_PEAK_GBS, 4), traffic=None,
+                    algorithmic_bytes=int(dm["bytes"]), avg_us=d["avg_us"])
+    else:
+        roof = dict(kernel=dominant, bound="mfma", achieved=d["TOPS"], peak=INT8_PEAK_TOPS, unit="TOP/s",
+                    frac=round(d["TOPS"] / INT8_PEAK_TOPS, 4), traffic=None,
+                    algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
+
+    Lr = L // n * r
+    ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
+    value = ops_step / (ms_per_step * 1e-3) / 1e12
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        Ls = min(L, max(n, args.cpu_sample_tokens // n * n))
+        xs, gys, wh = x[:Ls].cpu().numpy(), gy[:Ls].cpu().numpy(), w.cpu().numpy()
+        oracle.lib()
+        t0 = time.perf_counter()
+        codes, sx = oracle.compress_activation(xs, n, r)
+        oracle.backward_gx(gys, wh, n, bits=cfg.gx_bits, per_token=per_token, taps=False)
+        oracle.backward_gw(gys, codes, sx, n, r, taps=False)
+        dt = time.perf_counter() - t0
+        ops_s = 2 * Ls * O * I + 2 * O * I * (Ls // n * r)
+        cpu = dict(value=round(ops_s / dt / 1e12, 6), unit="TOPS", cores=oracle.threads(), kind="oracle",
+                   sample=f"first {Ls} of {L} tokens of {wl.name} (compress + g_x + g_w), {dt:.2f} s",
+                   seconds=round(dt, 3))
+
+    out = {
+        "metric": "HOT linear-backward effective TOPS (integer ops executed / step time)",
+        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
+                   "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
+                   "step": "compress_activation + linear_backward_gx + linear_backward_gw"},
+        "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -144,6 +144,23 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
                                  int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
                                  float* gy_scale, int32_t* acc, void* stream);
 
+/* ---- stage timing for benchmarks (off by default) ---- */
+
+/* Kernel roles timed separately; hot_debug_stage_name() gives their names. */
+#define HOT_NUM_STAGES 13
+
+/* From this call on, every kernel the library launches is bracketed by two HIP
+ * events recorded on its stream.  Host-side state only; not thread-safe against
+ * concurrent hot_* calls from other threads' streams being interleaved. */
+hot_status hot_debug_profile_begin(void);
+
+/* Stops recording, waits for the recorded events, and returns per stage the
+ * summed elapsed milliseconds and the number of launches (host arrays of
+ * HOT_NUM_STAGES entries). */
+hot_status hot_debug_profile_end(float* stage_ms, int64_t* stage_launches);
+
+const char* hot_debug_stage_name(int stage);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,8 +27,10 @@ EXPORTS = (
     "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
     "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
     "hot_select_quantizer", "hot_debug_unpack_activation", "hot_debug_gx_operands",
-    "hot_debug_gw_operands",
+    "hot_debug_gw_operands", "hot_debug_profile_begin", "hot_debug_profile_end",
+    "hot_debug_stage_name",
 )
+HOT_NUM_STAGES = 13
 
 
 class hot_config(C.Structure):
@@ -73,8 +75,12 @@ def lib() -> C.CDLL:
         l.hot_debug_unpack_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
         l.hot_debug_gx_operands.argtypes = [cfgp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp, vp]
         l.hot_debug_gw_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
-        for name in EXPORTS[4:]:
+        l.hot_debug_profile_begin.argtypes = []
+        l.hot_debug_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int64)]
+        for name in EXPORTS[4:-1]:
             getattr(l, name).restype = C.c_int
+        l.hot_debug_stage_name.argtypes = [C.c_int]
+        l.hot_debug_stage_name.restype = C.c_char_p
         _lib = l
     return _lib
 
@@ -233,3 +239,16 @@ def hot_debug_gw_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, 
                                      _ptr(sg), _ptr(acc), _stream(stream))
     _check(st, "hot_debug_gw_operands")
     return dict(qg=qg, sg=sg, acc=acc)
+
+
+def hot_debug_profile_begin() -> None:
+    _check(lib().hot_debug_profile_begin(), "hot_debug_profile_begin")
+
+
+def hot_debug_profile_end():
+    """Returns {stage name: (total ms, launches)} for the stages that ran."""
+    ms = (C.c_float * HOT_NUM_STAGES)()
+    cnt = (C.c_int64 * HOT_NUM_STAGES)()
+    _check(lib().hot_debug_profile_end(ms, cnt), "hot_debug_profile_end")
+    return {lib().hot_debug_stage_name(i).decode(): (float(ms[i]), int(cnt[i]))
+            for i in range(HOT_NUM_STAGES) if cnt[i]}

@@ -119,6 +119,14 @@ KeepMap identity_map(int n) {
   do {                                        \
     if ((expr) != hipSuccess) return HOT_ERR_DEVICE; \
   } while (0)
+// A launch bracketed by the optional stage timer.
+#define HOT_STAGE(stage, expr)                \
+  do {                                        \
+    stage_begin(stage, s);                    \
+    const hipError_t e_ = (expr);             \
+    stage_end(stage, s);                      \
+    if (e_ != hipSuccess) return HOT_ERR_DEVICE; \
+  } while (0)
 
 }  // namespace
 }  // namespace hot
@@ -185,9 +193,9 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   uint8_t* base = (uint8_t*)act_buf;
   float* scale = (float*)base;
   unsigned* amax = (unsigned*)base + 1;
-  HOT_TRY(launch_fill_u32((unsigned*)base, kHeaderBytes / 4, 0u, s));
-  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 1, nullptr, a.pitch, scale, amax, s));
-  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 2, base + a.codes, a.pitch, scale, amax, s));
+  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)base, kHeaderBytes / 4, 0u, s));
+  HOT_STAGE(kStActAbsmax, launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 1, nullptr, a.pitch, scale, amax, s));
+  HOT_STAGE(kStActQuant, launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 2, base + a.codes, a.pitch, scale, amax, s));
   return HOT_OK;
 }
 
@@ -213,19 +221,19 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   uint8_t* qw = base + g.qw;
   const KeepMap ident = identity_map(c.n);
 
-  HOT_TRY(launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
+  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
   // H.w along O, one scale, written as [I x O] code rows
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 1, nullptr, g.pitch, s_w, amax_w, s));
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 2, qw, g.pitch, s_w, amax_w, s));
+  HOT_STAGE(kStWAbsmax, launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 1, nullptr, g.pitch, s_w, amax_w, s));
+  HOT_STAGE(kStWQuant, launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 2, qw, g.pitch, s_w, amax_w, s));
   // g_y.H^T along O
   if (gy_quantizer == HOT_Q_PER_TOKEN) {
-    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, amax_g, s));
+    HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, amax_g, s));
   } else {
-    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, amax_g, s));
-    HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, amax_g, s));
+    HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, amax_g, s));
+    HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, amax_g, s));
   }
   HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, nullptr, g_x, s_g,
-                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s));
+                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
 
@@ -250,12 +258,12 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   int32_t* partial = g.split_k > 1 ? (int32_t*)(base + g.partial) : nullptr;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
-  HOT_TRY(launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
+  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
-  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 1, nullptr, g.pitch, s_g, amax_g, s));
-  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 2, qg, g.pitch, s_g, amax_g, s));
+  HOT_STAGE(kStGyTAbsmax, launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 1, nullptr, g.pitch, s_g, amax_g, s));
+  HOT_STAGE(kStGyTQuant, launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 2, qg, g.pitch, s_g, amax_g, s));
   HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.split_k, partial,
-                       nullptr, g_w, s_g, 0, (const float*)abase, c.n, s));
+                       nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
   return HOT_OK;
 }
 

@@ -59,6 +59,14 @@ SelLayout sel_layout(const Config& c, int64_t L, int64_t O);
 ActLayout act_layout(const Config& c, int64_t L, int64_t I);
 int gemm_split_k(int64_t M, int64_t N, int64_t k_bytes);
 
+// Kernel roles for the optional stage timer (names in profile.hip).
+enum Stage {
+  kStFill = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
+  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStGwReduce
+};
+void stage_begin(int stage, hipStream_t s);
+void stage_end(int stage, hipStream_t s);
+
 // ---- launchers (each returns hipGetLastError() of its launches) -------------
 
 // Row-direction block WHT + quantise of t [rows x cols] (cols % n == 0).
@@ -92,7 +100,8 @@ hipError_t launch_fill_u32(unsigned* p, int64_t count, unsigned value, hipStream
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
                         int64_t pitch, int bits, int split_k, int32_t* partial, int32_t* out_i32,
                         float* out_f32, const float* row_scale, int row_stride,
-                        const float* col_scale, int n, hipStream_t s);
+                        const float* col_scale, int n, hipStream_t s, int gemm_stage = -1,
+                        int reduce_stage = -1);
 
 // Unpack K-contiguous codes [rows x pitch] into one int8 per code.
 //   transpose = 0: out[row * K + k];  transpose = 1: out[k * rows + row].

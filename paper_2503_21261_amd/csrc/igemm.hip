@@ -218,7 +218,8 @@ int gemm_split_k(int64_t M, int64_t N, int64_t k_bytes) {
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
                         int64_t pitch, int bits, int split_k, int32_t* partial, int32_t* out_i32,
                         float* out_f32, const float* row_scale, int row_stride,
-                        const float* col_scale, int n, hipStream_t s) {
+                        const float* col_scale, int n, hipStream_t s, int gemm_stage,
+                        int reduce_stage) {
   if (M <= 0 || N <= 0) return hipSuccess;
   constexpr int BM = 128, BN = 128;
   const int nk = (int)(k_bytes / kBK);
@@ -230,6 +231,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   int32_t* k_i32 = split_k > 1 ? partial : out_i32;
   float* k_f32 = split_k > 1 ? nullptr : out_f32;
   if (split_k == 1 && out_i32 && out_f32) k_f32 = nullptr;  // int32 wins; caller asks one at a time
+  if (gemm_stage >= 0) stage_begin(gemm_stage, s);
   if (bits == 4)
     igemm_kernel<BM, BN, true><<<grid, dim3(256), 0, s>>>(A, B, (int)M, (int)N, nk, pitch, sps, tiles_m,
                                                          k_i32, k_f32, row_scale, row_stride,
@@ -238,13 +240,16 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
     igemm_kernel<BM, BN, false><<<grid, dim3(256), 0, s>>>(A, B, (int)M, (int)N, nk, pitch, sps, tiles_m,
                                                           k_i32, k_f32, row_scale, row_stride,
                                                           col_scale, inv_n);
+  if (gemm_stage >= 0) stage_end(gemm_stage, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || split_k == 1) return e;
   int64_t blocks = ceil_div(M * N, 256);
   if (blocks > 4096) blocks = 4096;
+  if (reduce_stage >= 0) stage_begin(reduce_stage, s);
   splitk_reduce_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
       partial, split_k, M, N, out_i32, out_i32 ? nullptr : out_f32, row_scale, row_stride,
       col_scale, inv_n);
+  if (reduce_stage >= 0) stage_end(reduce_stage, s);
   return hipGetLastError();
 }
 
