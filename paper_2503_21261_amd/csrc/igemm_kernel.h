@@ -1,0 +1,277 @@
+// Integer GEMM kernel on the CDNA4 matrix cores with fused dequantisation:
+//   C[M x N] = A[M x K] . B[N x K]^T,  both operands K-contiguous code rows.
+// g_x path (Sec. 5.1): A = Q(g_y H^T) [L x O], B = Q(H w)^T [I x O], INT4.
+// g_w path (Sec. 5.2): A = Q(HLA(g_y))^T [O x L'], B = x_hat^T [I x L'], INT8.
+//
+// v_mfma_i32_32x32x32_i8: a lane supplies 16 consecutive K bytes of row (lane%32)
+// for A and of column (lane%32) for B, K group lane/32; the same K mapping is
+// used for both operands, so only "same bytes on both sides" matters.  gfx950 has
+// no INT4 matrix instruction: packed nibbles are widened in registers to
+// 16 x code (low nibble: (d << 4) & 0xF0F0F0F0, high nibble: d & 0xF0F0F0F0, both
+// sign-correct as int8), so the accumulator is exactly 256 x the true sum and is
+// shifted back in the epilogue.  Packing halves global and LDS traffic.
+//
+// The dequantisation of Sec. 4.3 / Supp. F (a diagonal scaling) is the epilogue:
+// out = acc * row_scale[m] * col_scale / n.
+#pragma once
+#include <type_traits>
+#include <utility>
+
+#include "hot_device.h"
+
+namespace hot {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// Compile-time loop: f(std::integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
+
+struct GemmArgs {
+  const uint8_t* A;
+  const uint8_t* B;
+  int M, N;
+  int nk_total;          // K stages of BKB bytes in the whole K range
+  int stages_per_split;  // K stages handled by one blockIdx.z slice
+  int64_t pitch;         // bytes per operand row
+  int tiles_m, tiles_n;
+  int32_t* out_i32;      // raw accumulators [z][M][N], or
+  float* out_f32;        // dequantised output [M][N]
+  const float* row_scale;
+  int row_stride;
+  const float* col_scale;
+  float inv_n;
+};
+
+// Workgroup id -> output tile.  Workgroups are dealt round-robin to the 8 XCDs,
+// each with its own L2: ids are regrouped so that one XCD walks a contiguous run
+// of tiles, and within a run consecutive ids share the B tile (same tn) so the
+// small weight operand stays L2-resident while A streams.
+__device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& tn) {
+  const int total = g.tiles_m * g.tiles_n;
+  int id = blockIdx.x;
+  const int per_xcd = total / 8;
+  if (id < per_xcd * 8) id = (id % 8) * per_xcd + id / 8;
+  tm = id % g.tiles_m;
+  tn = id / g.tiles_m;
+}
+
+// ---- main loop ---------------------------------------------------------------------
+// One wave per SIMD at the large tile (the accumulators of a 128x128 wave tile fill
+// the AGPRs), so latency is hidden inside the wave rather than by occupancy:
+//   - global loads run two K stages ahead (registers), LDS holds two stages;
+//   - the 16-byte LDS fragments of K slice ks+1 are read, and (INT4) widened, while
+//     the matrix instructions of slice ks execute;
+//   - one barrier per stage, placed before the last slice, so the first fragments
+//     of the next stage are fetched under the last slice's matrix instructions;
+//   - the loop is branch-free (tail iterations re-load and re-store a valid stage),
+//     and every memory or widening instruction is pinned between two matrix
+//     instructions so the matrix pipe never drains while the wave issues them.
+template <int TM, int TN, bool INT4>
+struct Operands {            // what the matrix instructions of one K slice consume
+  v4i a[INT4 ? 2 : 1][TM];   // [low nibbles | high nibbles] or the int8 codes
+  v4i b[INT4 ? 2 : 1][TN];
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, bool INT4>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const GemmArgs g) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int LP = BKB + 16;
+  constexpr int TPR = BKB / 16;
+  constexpr int RPP = NT / TPR;
+  constexpr int PA = BM / RPP, PB = BN / RPP;
+  constexpr int KS = BKB / 32;
+  static_assert(BM % RPP == 0 && BN % RPP == 0, "loader passes");
+  static_assert(KS >= 2 && KS % 2 == 0, "pipeline needs an even number of K slices per stage");
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint8_t* As = smem;
+  uint8_t* Bs = smem + 2 * BM * LP;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  int tm, tn;
+  tile_of_block(g, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+  const int k_begin = blockIdx.z * g.stages_per_split;
+  int k_end = k_begin + g.stages_per_split;
+  if (k_end > g.nk_total) k_end = g.nk_total;
+  const int nk = k_end - k_begin;
+
+  const int lr = tid / TPR, lseg = (tid % TPR) * 16;
+  const uint8_t* a_src[PA];
+  const uint8_t* b_src[PB];
+#pragma unroll
+  for (int p = 0; p < PA; ++p) {
+    int row = m0 + lr + RPP * p;
+    row = row < g.M ? row : g.M - 1;
+    a_src[p] = g.A + (int64_t)row * g.pitch + lseg;
+  }
+#pragma unroll
+  for (int p = 0; p < PB; ++p) {
+    int row = n0 + lr + RPP * p;
+    row = row < g.N ? row : g.N - 1;
+    b_src[p] = g.B + (int64_t)row * g.pitch + lseg;
+  }
+  v4i ra[PA], rb[PB];
+  auto load_stage = [&](int kt) {
+    const int64_t off = (int64_t)kt * BKB;
+#pragma unroll
+    for (int p = 0; p < PA; ++p) ra[p] = *reinterpret_cast<const v4i*>(a_src[p] + off);
+#pragma unroll
+    for (int p = 0; p < PB; ++p) rb[p] = *reinterpret_cast<const v4i*>(b_src[p] + off);
+  };
+  auto store_stage = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < PA; ++p)
+      *reinterpret_cast<v4i*>(&As[buf * BM * LP + (lr + RPP * p) * LP + lseg]) = ra[p];
+#pragma unroll
+    for (int p = 0; p < PB; ++p)
+      *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + (lr + RPP * p) * LP + lseg]) = rb[p];
+  };
+
+  v16i acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+  const int a_off = (wm0 + (lane & 31)) * LP + (lane >> 5) * 16;
+  const int b_off = (wn0 + (lane & 31)) * LP + (lane >> 5) * 16;
+  v4i fa[TM], fb[TN];  // raw 16-byte fragments in flight (INT4 only)
+  // One K slice = NM matrix instructions; everything else the slice has to issue is
+  // cut into "events" that are emitted, in a fixed order, between those instructions:
+  //   slice 0 of a stage: NG x (LDS store of stage it+1, global load of stage it+2),
+  //   every slice: NR LDS fragment reads of the next slice, then (INT4) 2*NR widenings
+  //   of half a fragment each.  sched_barrier(0) after every step pins the order.
+  constexpr int NM = TM * TN * (INT4 ? 2 : 1);
+  constexpr int NR = TM + TN;
+  constexpr int NG = PA + PB;
+  constexpr int NW = INT4 ? 2 * NR : 0;
+
+  Operands<TM, TN, INT4> u0, u1;
+  // event bodies; every index is a compile-time constant so all arrays stay in registers
+  auto read_one = [&](Operands<TM, TN, INT4>& un, int buf, int ks, auto fc) {
+    constexpr int f = decltype(fc)::value;
+    v4i val;
+    if constexpr (f < TM) val = *reinterpret_cast<const v4i*>(&As[buf * BM * LP + a_off + f * 32 * LP + ks * 32]);
+    else val = *reinterpret_cast<const v4i*>(&Bs[buf * BN * LP + b_off + (f - TM) * 32 * LP + ks * 32]);
+    if constexpr (INT4) {
+      if constexpr (f < TM) fa[f] = val; else fb[f - TM] = val;
+    } else {
+      if constexpr (f < TM) un.a[0][f] = val; else un.b[0][f - TM] = val;
+    }
+  };
+  auto widen_half = [&](Operands<TM, TN, INT4>& un, auto ec) {  // two dwords of fragment e/2
+    if constexpr (INT4) {
+      constexpr int e = decltype(ec)::value;
+      constexpr int f = e >> 1, d0 = (e & 1) * 2;
+      static_for<2>([&](auto dc) {
+        constexpr int d = d0 + decltype(dc)::value;
+        if constexpr (f < TM) {
+          const unsigned x = (unsigned)fa[f][d];
+          un.a[0][f][d] = (int)((x << 4) & 0xF0F0F0F0u);
+          un.a[1][f][d] = (int)(x & 0xF0F0F0F0u);
+        } else {
+          const unsigned x = (unsigned)fb[f - TM][d];
+          un.b[0][f - TM][d] = (int)((x << 4) & 0xF0F0F0F0u);
+          un.b[1][f - TM][d] = (int)(x & 0xF0F0F0F0u);
+        }
+      });
+    }
+  };
+  auto store_one = [&](int buf, auto pc) {
+    constexpr int p = decltype(pc)::value;
+    if constexpr (p < PA) *reinterpret_cast<v4i*>(&As[buf * BM * LP + (lr + RPP * p) * LP + lseg]) = ra[p];
+    else *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + (lr + RPP * (p - PA)) * LP + lseg]) = rb[p - PA];
+  };
+  auto load_one = [&](int64_t off, auto pc) {
+    constexpr int p = decltype(pc)::value;
+    if constexpr (p < PA) ra[p] = *reinterpret_cast<const v4i*>(a_src[p] + off);
+    else rb[p - PA] = *reinterpret_cast<const v4i*>(b_src[p - PA] + off);
+  };
+  // one K slice: matrix instructions on `uc`, events that prepare `un`
+  auto slice = [&](auto ksc, Operands<TM, TN, INT4>& uc, Operands<TM, TN, INT4>& un, int cur,
+                   int nxt, int64_t off2) {
+    constexpr int ks = decltype(ksc)::value;
+    constexpr bool last = ks + 1 == KS;
+    constexpr int NS = ks == 0 ? 2 * NG : 0;   // store/load events come first
+    constexpr int NE = NS + NR + NW;
+    if constexpr (last) __syncthreads();  // everyone has written `nxt` and finished reading `cur`
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NM>([&](auto qc) {
+      constexpr int q = decltype(qc)::value;
+      constexpr int E0 = (q * NE + NM - 1) / NM;           // events e with e*NM < (q+1)*NE ...
+      constexpr int E1 = ((q + 1) * NE + NM - 1) / NM;     // ... not yet emitted
+      static_for<E1 - E0>([&](auto dc) {
+        constexpr int e = E0 + decltype(dc)::value;
+        if constexpr (e < NS) {
+          if constexpr ((e & 1) == 0) store_one(nxt, std::integral_constant<int, e / 2>{});
+          else load_one(off2, std::integral_constant<int, e / 2>{});
+        } else if constexpr (e < NS + NR) {
+          read_one(un, last ? nxt : cur, last ? 0 : ks + 1, std::integral_constant<int, e - NS>{});
+        } else {
+          widen_half(un, std::integral_constant<int, e - NS - NR>{});
+        }
+      });
+      constexpr int h = q / (TM * TN), i = (q % (TM * TN)) / TN, j = q % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(uc.a[h][i], uc.b[h][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
+  if (nk > 0) {
+    load_stage(k_begin);
+    store_stage(0);
+    load_stage(k_begin + (nk > 1 ? 1 : 0));
+    __syncthreads();
+    static_for<NR>([&](auto fc) { read_one(u0, 0, 0, fc); });
+    static_for<(NW > 0 ? NW : 1)>([&](auto ec) { widen_half(u0, ec); });
+    for (int it = 0; it < nk; ++it) {
+      const int cur = it & 1, nxt = cur ^ 1;
+      int kt2 = k_begin + it + 2;
+      kt2 = kt2 < k_end ? kt2 : k_end - 1;  // tail iterations re-load a valid stage (unused)
+      const int64_t off2 = (int64_t)kt2 * BKB;
+      static_for<KS>([&](auto ksc) {
+        constexpr int ks = decltype(ksc)::value;
+        if constexpr ((ks & 1) == 0) slice(ksc, u0, u1, cur, nxt, off2);
+        else slice(ksc, u1, u0, cur, nxt, off2);
+      });
+    }
+  }
+
+  const float cs = g.out_f32 ? (*g.col_scale) * g.inv_n : 0.0f;
+  const int64_t zoff = g.out_i32 ? (int64_t)blockIdx.z * g.M * (int64_t)g.N : 0;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (m >= g.M) continue;
+      const float rs = g.out_f32 ? g.row_scale[(int64_t)m * g.row_stride] * cs : 0.0f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn0 + j * 32 + (lane & 31);
+        if (n >= g.N) continue;
+        int c = acc[i][j][v];
+        if constexpr (INT4) c >>= 8;
+        const int64_t o = (int64_t)m * g.N + n;
+        if (g.out_f32) g.out_f32[o] = (float)c * rs;
+        else g.out_i32[zoff + o] = c;
+      }
+    }
+  }
+}
+
+}  // namespace hot
