@@ -83,6 +83,7 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
  *   x_hat = rows keep_idx of (H_n applied to every block of n consecutive tokens
  *   of x), INT8 with one abs-max scale for the tensor.
  * x: device [L x I] (in).  act_buf: device, hot_act_buffer_bytes() bytes (out).
+ * ws: scratch as for the other calls (the first 17 KB are used).
  * Requires L % n == 0, L*r/n <= 133144.
  */
 hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_t L, int64_t I,

@@ -157,11 +157,11 @@ def alloc_act_buffer(cfg: Config, L: int, I: int, device="cuda") -> torch.Tensor
 
 
 def hot_compress_activation(cfg: Config, x: torch.Tensor, act_buf: torch.Tensor,
-                            ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                            ws: torch.Tensor, stream=None) -> torch.Tensor:
     L, I = x.shape
     _dev_f32(x, (L, I), "x")
     st = lib().hot_compress_activation(C.byref(cfg.c()), _ptr(x), L, I, _ptr(act_buf), _ptr(ws),
-                                       0 if ws is None else ws.numel(), _stream(stream))
+                                       ws.numel(), _stream(stream))
     _check(st, "hot_compress_activation")
     return act_buf
 

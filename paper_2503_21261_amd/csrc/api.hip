@@ -62,7 +62,7 @@ GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GxLayout g;
   g.pitch = round_up(O * c.gx_bits / 8, kPitchAlign);
   g.scalars = 0;
-  g.sg = kHeaderBytes;
+  g.sg = kWsPrefix;
   g.qg = g.sg + (size_t)round_up(L * 4, 256);
   g.qw = g.qg + (size_t)(L * g.pitch);
   g.total = g.qw + (size_t)(I * g.pitch);
@@ -75,7 +75,7 @@ GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   g.pitch = round_up(g.Lr, kPitchAlign);
   g.split_k = gemm_split_k(O, I, g.pitch);
   g.scalars = 0;
-  g.qg = kHeaderBytes;
+  g.qg = kWsPrefix;
   g.partial = g.qg + (size_t)round_up(O * g.pitch, 256);
   g.total = g.partial + (g.split_k > 1 ? (size_t)g.split_k * O * I * 4 : 0);
   return g;
@@ -84,7 +84,7 @@ GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
 SelLayout sel_layout(const Config&, int64_t L, int64_t) {
   SelLayout s;
   s.scalars = 0;
-  s.rowmax = kHeaderBytes;
+  s.rowmax = kWsPrefix;
   s.partial = s.rowmax + (size_t)round_up(L * 4, 256);
   s.total = s.partial + (size_t)L * 16;
   return s;
@@ -168,7 +168,7 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
   Config c;
   if (resolve_config(cfg, &c) != HOT_OK) return 0;
   if (L < 1 || O < 1 || I < 1) return 0;
-  size_t need = kHeaderBytes;
+  size_t need = kWsPrefix;
   if (gx_shape_ok(c, L, O, I)) {
     const size_t a = gx_layout(c, L, O, I).total, b = sel_layout(c, L, O).total;
     need = a > need ? a : need;
@@ -182,20 +182,19 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
 }
 
 hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_t L, int64_t I,
-                                   void* act_buf, void* /*ws*/, size_t /*ws_bytes*/, void* stream) {
+                                   void* act_buf, void* ws, size_t ws_bytes, void* stream) {
   Config c;
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
-  if (!x || !act_buf || !aligned16(x) || !aligned16(act_buf)) return HOT_ERR_ARG;
+  if (!x || !act_buf || !ws || !aligned16(x) || !aligned16(act_buf) || !aligned16(ws)) return HOT_ERR_ARG;
   if (!tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  if (ws_bytes < (size_t)kWsPrefix) return HOT_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const ActLayout a = act_layout(c, L, I);
   uint8_t* base = (uint8_t*)act_buf;
-  float* scale = (float*)base;
-  unsigned* amax = (unsigned*)base + 1;
-  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)base, kHeaderBytes / 4, 0u, s));
-  HOT_STAGE(kStActAbsmax, launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 1, nullptr, a.pitch, scale, amax, s));
-  HOT_STAGE(kStActQuant, launch_col_quant(x, L, I, c, c.r, c.map, c.gw_bits, 2, base + a.codes, a.pitch, scale, amax, s));
+  float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
+  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, false, c.gw_bits, base + a.codes, a.pitch,
+                           (float*)base, partials, s, kStActAbsmax, kStActQuant));
   return HOT_OK;
 }
 
@@ -214,23 +213,23 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
   float* s_w = (float*)(base + g.scalars);
-  unsigned* amax_w = (unsigned*)(base + g.scalars) + 1;
-  unsigned* amax_g = (unsigned*)(base + g.scalars) + 2;
+  float* part_w = (float*)(base + kHeaderBytes);
+  float* part_g = (float*)(base + kHeaderBytes + kPartialBytes);
   float* s_g = (float*)(base + g.sg);
   uint8_t* qg = base + g.qg;
   uint8_t* qw = base + g.qw;
   const KeepMap ident = identity_map(c.n);
 
-  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
   // H.w along O, one scale, written as [I x O] code rows
-  HOT_STAGE(kStWAbsmax, launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 1, nullptr, g.pitch, s_w, amax_w, s));
-  HOT_STAGE(kStWQuant, launch_col_quant(w, O, I, c, c.n, ident, c.gx_bits, 2, qw, g.pitch, s_w, amax_w, s));
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, true, c.gx_bits, qw, g.pitch, s_w, part_w, s,
+                           kStWAbsmax, kStWQuant));
   // g_y.H^T along O
+  int npart = 0;
   if (gy_quantizer == HOT_Q_PER_TOKEN) {
-    HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, amax_g, s));
+    HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, part_g, &npart, s));
   } else {
-    HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, amax_g, s));
-    HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, amax_g, s));
+    HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
+    HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
   }
   HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, nullptr, g_x, s_g,
                        gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
@@ -253,15 +252,14 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
   float* s_g = (float*)(base + g.scalars);
-  unsigned* amax_g = (unsigned*)(base + g.scalars) + 1;
+  float* part_g = (float*)(base + kHeaderBytes);
   uint8_t* qg = base + g.qg;
   int32_t* partial = g.split_k > 1 ? (int32_t*)(base + g.partial) : nullptr;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
-  HOT_STAGE(kStFill, launch_fill_u32((unsigned*)(base + g.scalars), kHeaderBytes / 4, 0u, s));
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
-  HOT_STAGE(kStGyTAbsmax, launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 1, nullptr, g.pitch, s_g, amax_g, s));
-  HOT_STAGE(kStGyTQuant, launch_col_quant(g_y, L, O, c, c.r, c.map, c.gw_bits, 2, qg, g.pitch, s_g, amax_g, s));
+  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
+                           kStGyTAbsmax, kStGyTQuant));
   HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.split_k, partial,
                        nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
   return HOT_OK;
@@ -279,14 +277,14 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
   if (ws_bytes < l.total) return HOT_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
-  unsigned* amax = (unsigned*)(base + l.scalars) + 1;
+  float* part = (float*)(base + kHeaderBytes);
   double* result = (double*)(base + l.scalars + 64);
   float* rowmax = (float*)(base + l.rowmax);
   double* partial = (double*)(base + l.partial);
 
-  HOT_TRY(launch_fill_u32((unsigned*)(base + l.scalars), kHeaderBytes / 4, 0u, s));
-  HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 3, nullptr, 0, rowmax, amax, s));
-  HOT_TRY(launch_quant_error(g_y, L, O, c.n, c.gx_bits, c.rounding, rowmax, amax, partial, result, s));
+  int npart = 0;
+  HOT_TRY(launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 3, nullptr, 0, rowmax, part, &npart, s));
+  HOT_TRY(launch_quant_error(g_y, L, O, c.n, c.gx_bits, c.rounding, rowmax, part, npart, partial, result, s));
   double host[2] = {0.0, 0.0};
   HOT_TRY(hipMemcpyAsync(host, result, sizeof(host), hipMemcpyDeviceToHost, s));
   HOT_TRY(hipStreamSynchronize(s));

@@ -1,0 +1,213 @@
+// Column-direction block Walsh-Hadamard transform with row selection (HLA,
+// Sec. 3.3 Eq. 5), tensor-wide abs-max quantisation and a transposed,
+// K-contiguous write.  Serves three operands:
+//   - w rotated along O for the g_x path (Sec. 5.1): full rank, INT4/INT8;
+//   - x compressed along L at forward time (Sec. 5.2.1): r of n rows, INT8;
+//   - g_y compressed along L for the g_w path (Sec. 5.2): r of n rows, INT8.
+//
+// A lane owns VEC adjacent columns and holds the n rows of one block in
+// registers (n coalesced row loads in flight), so every butterfly is in-register.
+// Four waves take different blocks; their codes are gathered in LDS as
+// [column][reduced-row bytes] and written out as contiguous runs per column, so
+// the matrix-core GEMM that follows reads both operands K-contiguous and nothing
+// is ever transposed in a separate pass.  HBM-bound: the tensor-wide scale forces
+// two reads of the input (abs-max pass, quantise pass).  The abs-max pass leaves
+// one partial maximum per workgroup; the quantise pass reduces them itself, so no
+// atomics and no zero-initialised memory are needed.
+#pragma once
+#include "hot_device.h"
+#include "hot_host.h"
+
+namespace hot {
+
+template <int VEC> struct VecT;
+template <> struct VecT<1> { using type = float; };
+template <> struct VecT<2> { using type = float2; };
+template <> struct VecT<4> { using type = float4; };
+
+template <int VEC>
+__device__ __forceinline__ void unpack_vec(const typename VecT<VEC>::type& q, float (&o)[VEC]) {
+  if constexpr (VEC == 1) { o[0] = q; }
+  else if constexpr (VEC == 2) { o[0] = q.x; o[1] = q.y; }
+  else { o[0] = q.x; o[1] = q.y; o[2] = q.z; o[3] = q.w; }
+}
+
+// Natural-order index of the row of H_n with j sign changes: bit-reversed Gray code.
+__host__ __device__ constexpr int lowpass_row(int n, int j) {
+  const int g = j ^ (j >> 1);
+  int r = 0;
+  for (int b = 1, t = n >> 1; b < n; b <<= 1, t >>= 1)
+    if (g & b) r |= t;
+  return r;
+}
+
+// Which kept-row list the kernel was compiled for.
+enum KeepKind {
+  kKeepGeneric = 0,   // any list, from the KeepMap argument; INT8 codes, one LDS byte each
+  kKeepLowHalf = 1,   // the n/2 rows of lowest sequency, in sequency order; INT8
+  kKeepAll8 = 2,      // all rows, natural order; INT8
+  kKeepAll4 = 3,      // all rows, natural order; INT4, two codes per byte
+};
+
+// Load one block (N rows x VEC columns per lane) and transform it in registers.
+template <int N, int VEC>
+__device__ __forceinline__ void load_block_fwht(const float* __restrict__ src, int64_t C,
+                                                float (&v)[VEC][N]) {
+  using VT = typename VecT<VEC>::type;
+  VT q[N];
+#pragma unroll
+  for (int k = 0; k < N; ++k) q[k] = *reinterpret_cast<const VT*>(src + (int64_t)k * C);
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    float o[VEC];
+    unpack_vec<VEC>(q[k], o);
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) v[vi][k] = o[vi];
+  }
+#pragma unroll
+  for (int vi = 0; vi < VEC; ++vi) fwht_regs<N>(v[vi]);
+}
+
+// Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
+// grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
+template <int N, int VEC, int KIND>
+__global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, int64_t R,
+                                                         int64_t C, KeepMap map, int kbw,
+                                                         float* __restrict__ partials) {
+  constexpr int CT = 64 * VEC;
+  __shared__ float s_max[4];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t nblk = R / N;
+  const int64_t tiles_x = (C + CT - 1) / CT;
+  const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
+  float m = 0.0f;
+  for (int64_t t = blockIdx.x; t < tiles_x * tiles_y; t += gridDim.x) {
+    const int64_t tx = t % tiles_x, ty = t / tiles_x;
+    const int64_t c0 = tx * CT + lane * VEC;
+    if (c0 >= C) continue;
+    for (int kb = 0; kb < kbw; ++kb) {
+      const int64_t gb = ty * 4 * kbw + w * kbw + kb;
+      if (gb >= nblk) break;
+      float v[VEC][N];
+      load_block_fwht<N, VEC>(x + gb * N * C + c0, C, v);
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        bool kept;
+        if constexpr (KIND == kKeepGeneric) kept = map.pos[k] >= 0;
+        else if constexpr (KIND == kKeepLowHalf) kept = (k & 1) == 0;  // even natural rows
+        else kept = true;
+        if (kept) {
+#pragma unroll
+          for (int vi = 0; vi < VEC; ++vi) m = fmaxf(m, fabsf(v[vi][k]));
+        }
+      }
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) s_max[w] = m;
+  __syncthreads();
+  if (tid == 0) partials[blockIdx.x] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+}
+
+// Quantise pass: one tile per workgroup.  LDS tile: row (vi*64 + lane) holds the code
+// bytes of column lane*VEC + vi (odd dword pitch: conflict-free for both the strided
+// writes and the row-wise read-out).
+template <int N, int VEC, int KIND>
+__global__ __launch_bounds__(256) void col_quant_kernel(
+    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding, int kbw,
+    const float* __restrict__ partials, int npartials, uint8_t* __restrict__ codes, int64_t pitch,
+    float* __restrict__ scale) {
+  constexpr int CT = 64 * VEC;
+  constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  extern __shared__ __align__(16) uint8_t tile[];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
+  const int TB = 4 * kbw * bpb;      // code bytes per column in this tile
+  const int TBP = TB + 4;            // odd number of dwords
+  const int64_t nblk = R / N;
+  const int64_t tiles_x = (C + CT - 1) / CT;
+  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  const int64_t c0 = tx * CT + lane * VEC;
+  const bool col_ok = c0 < C;
+
+  const float amax = block_max_of(partials, npartials);
+  const float inv = quant_inv(amax, QMAX);
+  if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
+  // slots of blocks past the end must read back as zero codes
+  if ((ty + 1) * 4 * kbw > nblk) {
+    for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
+    __syncthreads();
+  }
+
+  for (int kb = 0; kb < kbw; ++kb) {
+    const int slot = w * kbw + kb;
+    const int64_t gb = ty * 4 * kbw + slot;
+    if (gb >= nblk || !col_ok) continue;
+    float v[VEC][N];
+    load_block_fwht<N, VEC>(x + gb * N * C + c0, C, v);
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) {
+      uint8_t* dst = tile + (vi * 64 + lane) * TBP + slot * bpb;
+      if constexpr (KIND == kKeepGeneric) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+          const int p = map.pos[k];
+          if (p >= 0) dst[p] = (uint8_t)quant_code(v[vi][k], inv, QMAX, rounding);
+        }
+      } else if constexpr (KIND == kKeepAll4) {
+#pragma unroll
+        for (int k8 = 0; k8 < N / 8; ++k8) {
+          uint32_t d = 0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            d |= (uint32_t)(quant_code(v[vi][k8 * 8 + e], inv, QMAX, rounding) & 0xF) << (4 * e);
+          reinterpret_cast<uint32_t*>(dst)[k8] = d;
+        }
+      } else {
+        constexpr int RK = KIND == kKeepLowHalf ? N / 2 : N;
+#pragma unroll
+        for (int j4 = 0; j4 < RK / 4; ++j4) {
+          uint32_t d = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int j = j4 * 4 + e;
+            const int k = KIND == kKeepLowHalf ? lowpass_row(N, j) : j;
+            d |= (uint32_t)(quant_code(v[vi][k], inv, QMAX, rounding) & 0xFF) << (8 * e);
+          }
+          reinterpret_cast<uint32_t*>(dst)[j4] = d;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // Contiguous runs per column; the last row tile also zero-fills up to the pitch.
+  const int64_t tile_off = ty * TB;
+  int64_t cover = (ty == (nblk + 4 * kbw - 1) / (4 * kbw) - 1) ? pitch - tile_off : TB;
+  if (cover > pitch - tile_off) cover = pitch - tile_off;
+  const int cdw = (int)(cover >> 2), tdw = TB >> 2;
+  for (int idx = tid; idx < CT * cdw; idx += 256) {
+    const int col = idx / cdw, dw = idx - col * cdw;
+    const int64_t c = tx * CT + col;
+    if (c < C) {
+      const int row = (col % VEC) * 64 + col / VEC;
+      const uint32_t val = dw < tdw ? *reinterpret_cast<const uint32_t*>(tile + row * TBP + 4 * dw) : 0u;
+      *reinterpret_cast<uint32_t*>(codes + c * pitch + tile_off + 4 * dw) = val;
+    }
+  }
+}
+
+// Host-side launch parameters shared by the two passes.
+struct ColPlan {
+  int kind;
+  int vec_a, kbw_a;     // abs-max pass: wide loads, few registers beyond the block itself
+  int absmax_grid;
+  int vec_q, kbw_q;     // quantise pass: narrow tiles, more waves in flight
+  int64_t tiles_q;
+  size_t lds_q;
+};
+
+ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity);
+
+}  // namespace hot

@@ -110,9 +110,19 @@ __device__ __forceinline__ int quant_code(float t, float inv, int qmax, int roun
   return min(max(q, -qmax), qmax);
 }
 
-// Non-negative floats order like their bit patterns: abs-max via integer atomicMax.
-__device__ __forceinline__ void atomic_absmax(unsigned* slot, float amax) {
-  atomicMax(slot, __float_as_uint(amax));
+// Maximum of partials[0..count), returned to every thread of a 256-thread workgroup.
+// The abs-max kernels leave one partial per workgroup; their consumers call this
+// first, so no atomics and no pre-zeroed memory are involved.
+__device__ __forceinline__ float block_max_of(const float* __restrict__ partials, int count) {
+  __shared__ float s_part[4];
+  float m = 0.0f;
+  for (int i = threadIdx.x; i < count; i += 256) m = fmaxf(m, partials[i]);
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
+  __syncthreads();
+  return m;
 }
 
 }  // namespace hot

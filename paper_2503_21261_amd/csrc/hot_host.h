@@ -31,6 +31,10 @@ hot_status resolve_config(const hot_config* cfg, Config* out);
 // K-contiguous operand rows are padded with zero codes to a multiple of 128 bytes.
 constexpr int64_t kPitchAlign = 128;
 constexpr int64_t kHeaderBytes = 256;
+// Every workspace starts with 256 bytes of scalars (scales, results) and two arrays
+// of per-workgroup partial maxima.
+constexpr int64_t kPartialBytes = 2048 * 4;
+constexpr int64_t kWsPrefix = kHeaderBytes + 2 * kPartialBytes;
 // |code products| summed over K must fit int32 (INT4 operands are fed to the
 // matrix cores as 16 x code, so their bound carries a factor 256).
 constexpr int64_t kMaxK8 = 133144;   // 127^2 * K < 2^31
@@ -69,28 +73,31 @@ void stage_end(int stage, hipStream_t s);
 
 // ---- launchers (each returns hipGetLastError() of its launches) -------------
 
+// Abs-max passes leave up to kMaxPartials per-workgroup maxima; consumers reduce them.
+constexpr int kMaxPartials = 2048;
+
 // Row-direction block WHT + quantise of t [rows x cols] (cols % n == 0).
 //   mode 0: per-token: codes + scales[rows].
-//   mode 1: abs-max of the rotated tensor into *amax_bits (atomic max, must be
-//           zeroed first); nothing else is written.
-//   mode 2: quantise with the tensor-wide abs-max in *amax_bits; scales[0] written.
-//   mode 3: abs-max per row into scales[rows] and tensor-wide into *amax_bits.
+//   mode 1: abs-max of the rotated tensor: partials[0..*npartials) written.
+//   mode 2: quantise with the tensor-wide abs-max = max(partials); scales[0] written.
+//   mode 3: abs-max per row into scales[rows] and tensor-wide into partials.
 // codes: rows x pitch bytes, `bits` = 4 (two codes per byte, even index in the
 // low nibble) or 8; bytes from cols*bits/8 up to pitch are zero-filled.
+// *npartials is written by modes 1/3 (host value) and read by mode 2.
 hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, int bits,
                             int rounding, int mode, uint8_t* codes, int64_t pitch, float* scales,
-                            unsigned* amax_bits, hipStream_t s);
+                            float* partials, int* npartials, hipStream_t s);
 
 // Column-direction block WHT (blocks of n consecutive rows of x [R x C]), keep r
 // rows per block, one scale for the tensor; output transposed: row c of `codes`
-// holds the kept values of column c, reduced row index contiguous.
-//   mode 1: abs-max of the kept rotated values into *amax_bits (atomic max).
-//   mode 2: quantise with *amax_bits; *scale written; pad bytes zero-filled.
+// holds the kept values of column c, reduced row index contiguous.  Runs the
+// abs-max pass (partials, kMaxPartials floats of scratch) and the quantise pass;
+// *scale is written, pad bytes up to `pitch` are zero-filled.  `identity` says the
+// kept list is 0..n-1 (required for bits == 4).
 hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& cfg, int r,
-                            const KeepMap& map, int bits, int mode, uint8_t* codes,
-                            int64_t pitch, float* scale, unsigned* amax_bits, hipStream_t s);
-
-hipError_t launch_fill_u32(unsigned* p, int64_t count, unsigned value, hipStream_t s);
+                            const KeepMap& map, bool identity, int bits, uint8_t* codes,
+                            int64_t pitch, float* scale, float* partials, hipStream_t s,
+                            int stage_absmax, int stage_quant);
 
 // C[M x N] = A[M x K] . B[N x K]^T on K-contiguous code rows (pitch bytes each,
 // k_bytes = K * bits / 8 rounded up to the pitch alignment).
@@ -109,10 +116,10 @@ hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t 
                          int transpose, int8_t* out, hipStream_t s);
 
 // Squared quantisation error of the rotated t [rows x cols] with per-token and
-// per-tensor scales (rowmax[rows], *amax_bits from launch_row_quant mode 3):
+// per-tensor scales (rowmax[rows] and partials from launch_row_quant mode 3):
 // result[0] = sum per-token, result[1] = sum per-tensor (double, fixed order).
 hipError_t launch_quant_error(const float* t, int64_t rows, int64_t cols, int n, int bits,
-                              int rounding, const float* rowmax, const unsigned* amax_bits,
-                              double* partial, double* result, hipStream_t s);
+                              int rounding, const float* rowmax, const float* partials,
+                              int npartials, double* partial, double* result, hipStream_t s);
 
 }  // namespace hot

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void row_quant_kernel(const float* __restrict_
                                                         int cols, int bits, int rounding, int mode,
                                                         uint8_t* __restrict__ codes, int64_t pitch,
                                                         float* __restrict__ scales,
-                                                        unsigned* __restrict__ amax_bits) {
+                                                        float* __restrict__ partials, int npartials) {
   constexpr int RPB = 256 / TPR;
   __shared__ float s_max[4];
   const int tid = threadIdx.x;
@@ -42,6 +42,8 @@ __global__ __launch_bounds__(256) void row_quant_kernel(const float* __restrict_
   const int64_t nrb = (rows + RPB - 1) / RPB;
   const int valid_bytes = cols * bits / 8;
   float running = 0.0f;  // modes 1, 3: abs-max over all rows this thread's group saw
+  float amax_tensor = 0.0f;
+  if (mode == 2) amax_tensor = block_max_of(partials, npartials);
 
   for (int64_t rb = blockIdx.x; rb < nrb; rb += gridDim.x) {
     const int64_t row = rb * RPB + rl;
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(256) void row_quant_kernel(const float* __restrict_
     }
     float amax;
     if (mode == 2) {
-      amax = __uint_as_float(*amax_bits);
+      amax = amax_tensor;
     } else {
       m = wave_max(m);
       if constexpr (TPR == 256) {
@@ -91,10 +93,13 @@ __global__ __launch_bounds__(256) void row_quant_kernel(const float* __restrict_
     }
   }
   if (mode == 1 || mode == 3) {
-    // every lane of a row group holds that group's maximum; one atomic per wave
-    if ((tid & 63) == 0) atomic_absmax(amax_bits, running);
+    // every lane of a row group holds that group's maximum; combine the groups
+    __syncthreads();
+    if ((tid & 63) == 0) s_max[tid >> 6] = running;
+    __syncthreads();
+    if (tid == 0) partials[blockIdx.x] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
   } else if (mode == 2 && blockIdx.x == 0 && tid == 0) {
-    scales[0] = quant_scale(__uint_as_float(*amax_bits), qmax);
+    scales[0] = quant_scale(amax_tensor, qmax);
   }
 }
 
@@ -104,18 +109,20 @@ template <int N>
 __global__ __launch_bounds__(256) void row_quant_stream_kernel(
     const float* __restrict__ t, int64_t rows, int cols, int bits, int rounding, int mode,
     uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scales,
-    unsigned* __restrict__ amax_bits) {
+    float* __restrict__ partials, int npartials) {
   __shared__ float s_max[4];
   const int tid = threadIdx.x;
   const int qmax = (1 << (bits - 1)) - 1;
   const int valid_bytes = cols * bits / 8;
   const int nvec = cols / 4;
   float running = 0.0f;
+  float amax_tensor = 0.0f;
+  if (mode == 2) amax_tensor = block_max_of(partials, npartials);
   for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
     const float4* src = reinterpret_cast<const float4*>(t + row * (int64_t)cols);
     float amax;
     if (mode == 2) {
-      amax = __uint_as_float(*amax_bits);
+      amax = amax_tensor;
     } else {
       float m = 0.0f;
       for (int base = 0; base < nvec; base += 256) {  // uniform trip count: shuffles stay converged
@@ -148,38 +155,28 @@ __global__ __launch_bounds__(256) void row_quant_stream_kernel(
       *reinterpret_cast<uint32_t*>(row_codes + off) = 0u;
   }
   if (mode == 1 || mode == 3) {
-    if (tid == 0) atomic_absmax(amax_bits, running);
+    if (tid == 0) partials[blockIdx.x] = running;
   } else if (mode == 2 && blockIdx.x == 0 && tid == 0) {
-    scales[0] = quant_scale(__uint_as_float(*amax_bits), qmax);
+    scales[0] = quant_scale(amax_tensor, qmax);
   }
-}
-
-__global__ void fill_u32_kernel(unsigned* p, int64_t count, unsigned value) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < count) p[i] = value;
-}
-
-hipError_t launch_fill_u32(unsigned* p, int64_t count, unsigned value, hipStream_t s) {
-  if (count <= 0) return hipSuccess;
-  fill_u32_kernel<<<dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, s>>>(p, count, value);
-  return hipGetLastError();
 }
 
 namespace {
 
-constexpr int kMaxGrid = 2048;  // grid-stride cap: bounds the atomics of the abs-max modes
+constexpr int kMaxGrid = kMaxPartials;  // abs-max modes: one partial maximum per workgroup
 
 template <int N>
 hipError_t dispatch_row_quant(const float* t, int64_t rows, int cols, int bits, int rounding,
                               int mode, uint8_t* codes, int64_t pitch, float* scales,
-                              unsigned* amax_bits, hipStream_t s) {
+                              float* partials, int* npartials, hipStream_t s) {
 #define HOT_LAUNCH(ITER, TPR)                                                                  \
   {                                                                                            \
     const int64_t nrb = ceil_div(rows, 256 / TPR);                                             \
     const unsigned grid = (unsigned)((mode == 1 || mode == 3) ? (nrb < kMaxGrid ? nrb : kMaxGrid) \
                                                               : (nrb < (1 << 20) ? nrb : (1 << 20))); \
+    if (mode == 1 || mode == 3) *npartials = (int)grid;                                        \
     row_quant_kernel<N, ITER, TPR><<<dim3(grid), dim3(256), 0, s>>>(                           \
-        t, rows, cols, bits, rounding, mode, codes, pitch, scales, amax_bits);                 \
+        t, rows, cols, bits, rounding, mode, codes, pitch, scales, partials, *npartials);      \
     return hipGetLastError();                                                                  \
   }
   const int v64 = (int)ceil_div(cols, 256);    // float4 per thread with one wave per row
@@ -197,8 +194,9 @@ hipError_t dispatch_row_quant(const float* t, int64_t rows, int cols, int bits, 
   if (v256 <= 16) HOT_LAUNCH(16, 256)
 #undef HOT_LAUNCH
   const unsigned grid = (unsigned)(rows < kMaxGrid ? rows : kMaxGrid);
+  if (mode == 1 || mode == 3) *npartials = (int)grid;
   row_quant_stream_kernel<N><<<dim3(grid), dim3(256), 0, s>>>(t, rows, cols, bits, rounding, mode,
-                                                              codes, pitch, scales, amax_bits);
+                                                              codes, pitch, scales, partials, *npartials);
   return hipGetLastError();
 }
 
@@ -206,12 +204,12 @@ hipError_t dispatch_row_quant(const float* t, int64_t rows, int cols, int bits, 
 
 hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, int bits,
                             int rounding, int mode, uint8_t* codes, int64_t pitch, float* scales,
-                            unsigned* amax_bits, hipStream_t s) {
+                            float* partials, int* npartials, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   switch (n) {
-    case 16: return dispatch_row_quant<16>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
-    case 32: return dispatch_row_quant<32>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
-    case 64: return dispatch_row_quant<64>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, amax_bits, s);
+    case 16: return dispatch_row_quant<16>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, partials, npartials, s);
+    case 32: return dispatch_row_quant<32>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, partials, npartials, s);
+    case 64: return dispatch_row_quant<64>(t, rows, (int)cols, bits, rounding, mode, codes, pitch, scales, partials, npartials, s);
   }
   return hipErrorInvalidValue;
 }

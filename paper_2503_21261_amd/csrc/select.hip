@@ -23,13 +23,13 @@ __device__ __forceinline__ double wave_sum(double v) {
 template <int N>
 __global__ __launch_bounds__(256) void quant_error_rows_kernel(
     const float* __restrict__ t, int64_t rows, int cols, int bits, int rounding,
-    const float* __restrict__ rowmax, const unsigned* __restrict__ amax_bits,
+    const float* __restrict__ rowmax, const float* __restrict__ partials, int npartials,
     double* __restrict__ partial) {
   __shared__ double s_sum[2][4];
   const int tid = threadIdx.x;
   const int qmax = (1 << (bits - 1)) - 1;
   const int nvec = cols / 4;
-  const float amax_ten = __uint_as_float(*amax_bits);
+  const float amax_ten = block_max_of(partials, npartials);
   const float inv_ten = quant_inv(amax_ten, qmax), sc_ten = quant_scale(amax_ten, qmax);
   for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
     const float4* src = reinterpret_cast<const float4*>(t + row * (int64_t)cols);
@@ -78,13 +78,13 @@ __global__ __launch_bounds__(256) void quant_error_final_kernel(const double* __
 }
 
 hipError_t launch_quant_error(const float* t, int64_t rows, int64_t cols, int n, int bits,
-                              int rounding, const float* rowmax, const unsigned* amax_bits,
-                              double* partial, double* result, hipStream_t s) {
+                              int rounding, const float* rowmax, const float* partials,
+                              int npartials, double* partial, double* result, hipStream_t s) {
   const unsigned grid = (unsigned)(rows < 4096 ? rows : 4096);
   switch (n) {
-    case 16: quant_error_rows_kernel<16><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, amax_bits, partial); break;
-    case 32: quant_error_rows_kernel<32><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, amax_bits, partial); break;
-    case 64: quant_error_rows_kernel<64><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, amax_bits, partial); break;
+    case 16: quant_error_rows_kernel<16><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, partials, npartials, partial); break;
+    case 32: quant_error_rows_kernel<32><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, partials, npartials, partial); break;
+    case 64: quant_error_rows_kernel<64><<<dim3(grid), dim3(256), 0, s>>>(t, rows, (int)cols, bits, rounding, rowmax, partials, npartials, partial); break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();

@@ -86,8 +86,9 @@ def test_argument_shape_and_workspace_errors_precede_any_launch():
     assert lib.hot_linear_backward_gw(c, fake, fake, 16 * 2 * 133152, 64, 64, fake, fake, big, None) == hot.HOT_ERR_SHAPE
     assert lib.hot_linear_backward_gw(c, fake, fake, 64, 64, 64, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
     assert lib.hot_linear_backward_gw(c, fake, None, 64, 64, 64, fake, fake, big, None) == hot.HOT_ERR_ARG
-    assert lib.hot_compress_activation(c, fake, 40, 64, fake, None, 0, None) == hot.HOT_ERR_SHAPE
-    assert lib.hot_compress_activation(c, None, 64, 64, fake, None, 0, None) == hot.HOT_ERR_ARG
+    assert lib.hot_compress_activation(c, fake, 40, 64, fake, fake, big, None) == hot.HOT_ERR_SHAPE
+    assert lib.hot_compress_activation(c, fake, 64, 64, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
+    assert lib.hot_compress_activation(c, None, 64, 64, fake, fake, big, None) == hot.HOT_ERR_ARG
     ch = C.c_int(0)
     assert lib.hot_select_quantizer(c, fake, 64, 64, None, None, None, fake, big, None) == hot.HOT_ERR_ARG
     assert lib.hot_select_quantizer(c, fake, 64, 70, C.byref(ch), None, None, fake, big, None) == hot.HOT_ERR_SHAPE
@@ -100,4 +101,4 @@ def test_binding_refuses_host_tensors():
     cfg = hot.Config()
     x = torch.zeros(64, 64)
     with pytest.raises(ValueError):
-        hot.hot_compress_activation(cfg, x, torch.zeros(10, dtype=torch.uint8))
+        hot.hot_compress_activation(cfg, x, torch.zeros(10, dtype=torch.uint8), torch.zeros(10, dtype=torch.uint8))

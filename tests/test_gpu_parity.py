@@ -73,7 +73,7 @@ def check_gw(hot, cfg, gy, x, what):
     gyd, xd = gy.cuda(), x.cuda()
     act = hot.alloc_act_buffer(cfg, L, I)
     ws = hot.alloc_workspace(cfg, L, O, I)
-    hot.hot_compress_activation(cfg, xd, act)
+    hot.hot_compress_activation(cfg, xd, act, ws)
     codes, sx = hot.hot_debug_unpack_activation(cfg, act, L, I)
     gw = torch.empty((O, I), dtype=torch.float32, device="cuda")
     hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
@@ -247,10 +247,89 @@ def test_calls_are_repeatable_and_stream_ordered():
         gx = torch.empty((L, I), device="cuda")
         gw = torch.empty((O, I), device="cuda")
         with torch.cuda.stream(s):
-            hot.hot_compress_activation(cfg, xd, act, stream=s)
+            hot.hot_compress_activation(cfg, xd, act, ws, stream=s)
             hot.hot_linear_backward_gx(cfg, gyd, wd, hot.HOT_Q_PER_TOKEN, gx, ws, stream=s)
             hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws, stream=s)
         s.synchronize()
         outs.append((gx.cpu().numpy().copy(), gw.cpu().numpy().copy()))
     for gx, gw in outs[1:]:
         assert np.array_equal(gx, outs[0][0]) and np.array_equal(gw, outs[0][1])
+
+
+# ---- full-size and workload-shaped cases -------------------------------------------------
+
+def test_config2_full_size_in_bench_configuration():
+    """configs[1] (ViT-B fc1, 12608 tokens, n=32, r=16) exactly as bench.py launches it;
+    the oracle is fast enough to compare every element of every stage."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg2_vitb_fc1"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    check_gx(hot, cfg, gy, w, True, "cfg2 per-token")
+    check_gx(hot, cfg, gy, w, False, "cfg2 per-tensor")
+    check_gw(hot, cfg, gy, x, "cfg2")
+    L, I = x.shape
+    # 12.5 % of fp32 plus the row padding to 128 bytes and the header
+    assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((L // 2 + 127) // 128 * 128)
+
+
+@pytest.mark.parametrize("name,L", [("cfg3_vitb_block_b256", 1024), ("cfg4_llm7b_mlp", 256),
+                                    ("cfg5_vitl_chain", 512)])
+def test_workload_shaped_layers_on_a_token_subrange(name, L):
+    """Layers of configs[2..4] at their real O, I, block and value distributions on a
+    token sub-range the oracle finishes in seconds; config 4 takes its quantizer from
+    hot_select_quantizer, which must agree with the oracle's choice."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS[name]
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    for layer in wl.layers:
+        x, w, gy = hot_inputs.make_layer(wl, layer, seed=0, L=L)
+        per_token = wl.quantizer == "token"
+        if wl.quantizer == "select":
+            ws = hot.alloc_workspace(cfg, L, layer.O, layer.I)
+            choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, gy.cuda(), ws)
+            ref_choice, r_tok, r_ten = oracle.select_quantizer(gy.numpy(), wl.block)
+            assert choice == int(ref_choice)
+            np.testing.assert_allclose([m_tok, m_ten], [r_tok, r_ten], rtol=1e-10)
+            per_token = bool(choice)
+            _say(f"[select] {name}.{layer.name}: {'token' if per_token else 'tensor'} "
+                 f"mse_token={m_tok:.3e} mse_tensor={m_ten:.3e}")
+        check_gx(hot, cfg, gy, w, per_token, f"{name}.{layer.name}")
+        check_gw(hot, cfg, gy, x, f"{name}.{layer.name}")
+
+
+def test_large_token_count_sampled_rows():
+    """configs[2] proj at its full 50432 tokens: every code and scale is compared with the
+    oracle; the integer product is checked exactly on sampled token rows (oracle GEMM on
+    those rows) and on all rows through an exact int64 Freivalds identity C v = A (B v)."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg3_vitb_block_b256"]
+    layer = wl.layers[1]
+    L, O, I = layer.L, layer.O, layer.I
+    x, w, gy = hot_inputs.make_layer(wl, layer, seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    _say(f"[gx] cfg3 proj full L={L} O={O} I={I}")
+    T = oracle.transform_rows(gy.numpy(), cfg.block)
+    qg_ref, sg_ref = oracle.quantize(T, 4, True, oracle.PSEUDO_STOCHASTIC)
+    U = oracle.hla(w.numpy(), cfg.block, cfg.block, np.arange(cfg.block))
+    qw_ref, sw_ref = oracle.quantize(U, 4, False, oracle.PSEUDO_STOCHASTIC)
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    gx = torch.empty((L, I), device="cuda")
+    hot.hot_linear_backward_gx(cfg, gy.cuda(), w.cuda(), hot.HOT_Q_PER_TOKEN, gx, ws)
+    taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, hot.HOT_Q_PER_TOKEN)
+    torch.cuda.synchronize()
+    assert np.array_equal(taps["qg"].cpu().numpy(), qg_ref)
+    assert bits_equal(taps["sg"].cpu().numpy(), sg_ref)
+    assert np.array_equal(taps["qw"].cpu().numpy(), qw_ref)
+    assert bits_equal(taps["sw"].cpu().numpy(), sw_ref)
+    acc = taps["acc"].cpu().numpy().astype(np.int64)
+    rng = np.random.default_rng(5)
+    v = rng.integers(-2048, 2048, size=I)
+    assert np.array_equal(acc @ v, qg_ref.astype(np.int64) @ (qw_ref.astype(np.int64) @ v))
+    u = rng.integers(-2048, 2048, size=L)
+    assert np.array_equal(u @ acc, (u @ qg_ref.astype(np.int64)) @ qw_ref.astype(np.int64))
+    rows = np.unique(np.concatenate([np.arange(0, 256), rng.integers(0, L, 512), np.arange(L - 200, L)]))
+    acc_rows, _ = oracle.igemm_nn(qg_ref[rows], qw_ref)
+    assert np.array_equal(acc[rows], acc_rows)
+    ref_rows = oracle.dequant(acc_rows, sg_ref[rows], sw_ref[0], cfg.block)
+    assert_close_maxnorm(gx.cpu().numpy()[rows], ref_rows, "cfg3 proj g_x rows")
