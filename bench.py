@@ -43,6 +43,35 @@ def stage_model(L, O, I, n, r, gx_bits, per_token):
     return m
 
 
+def probe_peaks(torch, hot):
+    """Plain HBM read / write rate and raw int8 matrix rate of this machine (context only)."""
+    out = {}
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(kind, buf, iters, reps):
+        hot.hot_debug_probe(kind, buf, iters)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(reps):
+            hot.hot_debug_probe(kind, buf, iters)
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / reps * 1e-3
+
+    for mb in (155, 1024):
+        buf = torch.zeros(mb * 1000 * 1000 // 4, dtype=torch.float32, device="cuda")
+        nbytes = buf.numel() * 4 - 4096
+        out[f"hbm_read_GBps_{mb}MB"] = round(nbytes / timed(0, buf, 1, 10) / 1e9, 1)
+        out[f"hbm_write_GBps_{mb}MB"] = round(nbytes / timed(1, buf, 1, 10) / 1e9, 1)
+        del buf
+    buf = torch.zeros(1 << 20, dtype=torch.int32, device="cuda")
+    iters = 4000
+    ops = 2.0 * 32 * 32 * 32 * 16 * iters * 256 * 4
+    out["mfma_i8_TOPS_constant_operands"] = round(ops / timed(2, buf, iters, 3) / 1e12, 1)
+    out["mfma_i8_TOPS_random_operands"] = round(ops / timed(3, buf, iters, 6) / 1e12, 1)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +84,9 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="repeat the oracle on the sample until about this much CPU wall time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-peaks", action="store_true",
+                    help="instead of the workload, time plain HBM read/write and a register-only "
+                         "int8 matrix loop, and print them as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of g_y (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -69,6 +101,9 @@ def main() -> int:
 
     hot.lib()  # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if args.probe_peaks:
+        print(json.dumps(probe_peaks(torch, hot)))
+        return 0
     wl = hot_inputs.WORKLOADS[args.workload]
     layer = wl.layers[0]
     L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep

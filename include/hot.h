@@ -162,6 +162,12 @@ hot_status hot_debug_profile_end(float* stage_ms, int64_t* stage_launches);
 
 const char* hot_debug_stage_name(int stage);
 
+/* Machine-peak probes (context for the roofline figures, not the method): one launch of
+ * kind 0 = read `bytes` of buf, 1 = write them, 2 / 3 = `iters` x 16 int8 32x32x32 matrix
+ * instructions per wave on all SIMDs with constant / pseudo-random register operands
+ * (buf, >= 1 MiB, receives a checksum).  The caller times the launch. */
+hot_status hot_debug_probe(int kind, void* buf, size_t bytes, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = (
     "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
     "hot_select_quantizer", "hot_debug_unpack_activation", "hot_debug_gx_operands",
     "hot_debug_gw_operands", "hot_debug_profile_begin", "hot_debug_profile_end",
-    "hot_debug_stage_name",
+    "hot_debug_stage_name", "hot_debug_probe",
 )
 HOT_NUM_STAGES = 13
 
@@ -77,8 +77,10 @@ def lib() -> C.CDLL:
         l.hot_debug_gw_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
         l.hot_debug_profile_begin.argtypes = []
         l.hot_debug_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int64)]
-        for name in EXPORTS[4:-1]:
-            getattr(l, name).restype = C.c_int
+        l.hot_debug_probe.argtypes = [C.c_int, vp, sz, C.c_int, vp]
+        for name in EXPORTS[4:]:
+            if name != "hot_debug_stage_name":
+                getattr(l, name).restype = C.c_int
         l.hot_debug_stage_name.argtypes = [C.c_int]
         l.hot_debug_stage_name.restype = C.c_char_p
         _lib = l
@@ -252,3 +254,8 @@ def hot_debug_profile_end():
     _check(lib().hot_debug_profile_end(ms, cnt), "hot_debug_profile_end")
     return {lib().hot_debug_stage_name(i).decode(): (float(ms[i]), int(cnt[i]))
             for i in range(HOT_NUM_STAGES) if cnt[i]}
+
+
+def hot_debug_probe(kind: int, buf: torch.Tensor, iters: int = 1, stream=None) -> None:
+    _check(lib().hot_debug_probe(int(kind), _ptr(buf), buf.numel() * buf.element_size(), int(iters),
+                                 _stream(stream)), "hot_debug_probe")

@@ -103,6 +103,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   static_assert(BM % RPP == 0 && BN % RPP == 0, "loader passes");
   static_assert(KS >= 2 && KS % 2 == 0, "pipeline needs an even number of K slices per stage");
   extern __shared__ __align__(16) uint8_t smem[];
+  __shared__ float s_rowfac[BM];   // row_scale[m] * col_scale / n for the rows of this tile
   uint8_t* As = smem;
   uint8_t* Bs = smem + 2 * BM * LP;
 
@@ -115,6 +116,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   int k_end = k_begin + g.stages_per_split;
   if (k_end > g.nk_total) k_end = g.nk_total;
   const int nk = k_end - k_begin;
+  if (g.out_f32) {  // visible to every wave after the barrier that follows the first LDS stage
+    const float cs = (*g.col_scale) * g.inv_n;
+    for (int i = tid; i < BM; i += NT)
+      s_rowfac[i] = m0 + i < g.M ? g.row_scale[(int64_t)(m0 + i) * g.row_stride] * cs : 0.0f;
+  }
+  __syncthreads();
 
   const int lr = tid / TPR, lseg = (tid % TPR) * 16;
   const uint8_t* a_src[PA];
@@ -260,15 +267,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
     }
   }
 
-  const float cs = g.out_f32 ? (*g.col_scale) * g.inv_n : 0.0f;
+  // Epilogue.  Accumulator register v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4,
+  // column lane%32, so each register is stored as 32-float (128-byte) row segments.
+  // The row factors come from LDS (filled before the main loop): a global load per row
+  // here could not be hoisted above the output stores and would serialise on L2 latency.
   const int64_t zoff = g.out_i32 ? (int64_t)blockIdx.z * g.M * (int64_t)g.N : 0;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int m = m0 + ml;
       if (m >= g.M) continue;
-      const float rs = g.out_f32 ? g.row_scale[(int64_t)m * g.row_stride] * cs : 0.0f;
+      const float rs = s_rowfac[ml];
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn0 + j * 32 + (lane & 31);
