@@ -73,11 +73,11 @@ GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GwLayout g;
   g.Lr = L / c.n * c.r;
   g.pitch = round_up(g.Lr, kPitchAlign);
-  g.split_k = gemm_split_k(O, I, g.pitch);
+  g.plan = plan_gemm(O, I, g.pitch, c.gw_bits, true);
   g.scalars = 0;
   g.qg = kWsPrefix;
   g.partial = g.qg + (size_t)round_up(O * g.pitch, 256);
-  g.total = g.partial + (g.split_k > 1 ? (size_t)g.split_k * O * I * 4 : 0);
+  g.total = g.partial + g.plan.partial_bytes;
   return g;
 }
 
@@ -231,7 +231,8 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
     HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
     HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
   }
-  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, nullptr, g_x, s_g,
+  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits,
+                       plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
                        gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
@@ -254,13 +255,13 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   float* s_g = (float*)(base + g.scalars);
   float* part_g = (float*)(base + kHeaderBytes);
   uint8_t* qg = base + g.qg;
-  int32_t* partial = g.split_k > 1 ? (int32_t*)(base + g.partial) : nullptr;
+  int32_t* partial = g.plan.split > 1 ? (int32_t*)(base + g.partial) : nullptr;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
   HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
                            kStGyTAbsmax, kStGyTQuant));
-  HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.split_k, partial,
+  HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.plan, partial,
                        nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
   return HOT_OK;
 }
@@ -332,8 +333,9 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t 
                            hipMemcpyDeviceToDevice, s));
   if (w_scale) HOT_TRY(hipMemcpyAsync(w_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(launch_igemm(base + g.qg, base + g.qw, L, I, g.pitch, g.pitch, c.gx_bits, 1, nullptr, acc,
-                         nullptr, nullptr, 0, nullptr, c.n, s));
+    HOT_TRY(launch_igemm(base + g.qg, base + g.qw, L, I, g.pitch, g.pitch, c.gx_bits,
+                         plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, acc, nullptr, nullptr,
+                         0, nullptr, c.n, s));
   return HOT_OK;
 }
 
@@ -352,8 +354,9 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
   if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, 8, 1, gy_codes, s));
   if (gy_scale) HOT_TRY(hipMemcpyAsync(gy_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch, 8, 1,
-                         nullptr, acc, nullptr, nullptr, 0, nullptr, c.n, s));
+    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch, 8,
+                         plan_gemm(O, I, g.pitch, 8, false), nullptr, acc, nullptr, nullptr, 0,
+                         nullptr, c.n, s));
   return HOT_OK;
 }
 

@@ -40,13 +40,21 @@ constexpr int64_t kWsPrefix = kHeaderBytes + 2 * kPartialBytes;
 constexpr int64_t kMaxK8 = 133144;   // 127^2 * K < 2^31
 constexpr int64_t kMaxK4 = 171196;   // 256 * 7^2 * K < 2^31
 
+// Tile shape and K split of one GEMM launch (a pure function of the shape).
+struct GemmPlan {
+  int bm, bn, bkb, split;
+  int64_t tiles;
+  size_t partial_bytes;   // split > 1: tiles * split * bm * bn int32
+};
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_split);
+
 struct GxLayout {
   int64_t pitch;                      // bytes per operand row (K = O codes)
   size_t scalars, sg, qg, qw, total;  // byte offsets into ws
 };
 struct GwLayout {
   int64_t Lr, pitch;                  // reduced token count, bytes per operand row
-  int split_k;
+  GemmPlan plan;
   size_t scalars, qg, partial, total;
 };
 struct SelLayout {
@@ -61,7 +69,7 @@ GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I);
 GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I);
 SelLayout sel_layout(const Config& c, int64_t L, int64_t O);
 ActLayout act_layout(const Config& c, int64_t L, int64_t I);
-int gemm_split_k(int64_t M, int64_t N, int64_t k_bytes);
+
 
 // Kernel roles for the optional stage timer (names in profile.hip).
 enum Stage {
@@ -103,10 +111,11 @@ hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& 
 // k_bytes = K * bits / 8 rounded up to the pitch alignment).
 //   out_i32 != NULL: raw int32 accumulators, row-major [M x N].
 //   out_f32 != NULL: out = acc * row_scale[m * row_stride] * (*col_scale) / n.
-// split_k > 1 accumulates K-slices in `partial` ([split_k x M x N] int32) first.
+// plan.split > 1 needs `partial` (plan.partial_bytes): each K slice leaves its
+// accumulators there and a second kernel adds them in slice order.
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
-                        int64_t pitch, int bits, int split_k, int32_t* partial, int32_t* out_i32,
-                        float* out_f32, const float* row_scale, int row_stride,
+                        int64_t pitch, int bits, const GemmPlan& plan, int32_t* partial,
+                        int32_t* out_i32, float* out_f32, const float* row_scale, int row_stride,
                         const float* col_scale, int n, hipStream_t s, int gemm_stage = -1,
                         int reduce_stage = -1);
 

@@ -43,8 +43,10 @@ struct GemmArgs {
   int stages_per_split;  // K stages handled by one blockIdx.z slice
   int64_t pitch;         // bytes per operand row
   int tiles_m, tiles_n;
-  int32_t* out_i32;      // raw accumulators [z][M][N], or
+  int32_t* out_i32;      // raw accumulators [M][N], or
   float* out_f32;        // dequantised output [M][N]
+  int split;             // K slices (gridDim.z); > 1: accumulators go to `partial`
+  int32_t* partial;      // [tile][slice][register image of the 256-thread tile]
   const float* row_scale;
   int row_stride;
   const float* col_scale;
@@ -267,11 +269,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
     }
   }
 
+  // Split-K: every slice stores its accumulators as a register image (fully coalesced);
+  // a second kernel adds the images in slice order and applies the epilogue.
+  if (g.split > 1) {
+    const int tile_id = tm * g.tiles_n + tn;
+    constexpr int IMG = BM * BN;
+    int32_t* mine = g.partial + ((int64_t)tile_id * g.split + blockIdx.z) * IMG;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          mine[((i * TN + j) * 16 + v) * NT + tid] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
+    return;
+  }
+
   // Epilogue.  Accumulator register v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32, so each register is stored as 32-float (128-byte) row segments.
   // The row factors come from LDS (filled before the main loop): a global load per row
   // here could not be hoisted above the output stores and would serialise on L2 latency.
-  const int64_t zoff = g.out_i32 ? (int64_t)blockIdx.z * g.M * (int64_t)g.N : 0;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -288,8 +305,49 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
         if constexpr (INT4) c >>= 8;
         const int64_t o = (int64_t)m * g.N + n;
         if (g.out_f32) g.out_f32[o] = (float)c * rs;
-        else g.out_i32[zoff + o] = c;
+        else g.out_i32[o] = c;
       }
+    }
+  }
+}
+
+
+// Second half of a split-K GEMM: out[m][n] = epilogue(sum over slices of the register
+// images the GEMM left), slices added in order (exact in int32).  One workgroup handles
+// 16 of the 16*TM*TN accumulator registers of one tile; reads and writes are the same
+// coalesced patterns the GEMM itself uses.
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(256) void splitk_image_reduce_kernel(const GemmArgs g) {
+  constexpr int NT = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TN = WN / 32;
+  constexpr int IMG = BM * BN;
+  constexpr int QPB = 16;                       // registers per workgroup
+  constexpr int BPT = IMG / NT / QPB;           // workgroups per tile
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tile_id = blockIdx.x / BPT, q0 = (blockIdx.x % BPT) * QPB;
+  const int tm = tile_id / g.tiles_n, tn = tile_id % g.tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+  const float cs = g.out_f32 ? (*g.col_scale) * g.inv_n : 0.0f;
+  const int32_t* img = g.partial + (int64_t)tile_id * g.split * IMG;
+  int sum[QPB];
+#pragma unroll
+  for (int k = 0; k < QPB; ++k) sum[k] = 0;
+  for (int z = 0; z < g.split; ++z, img += IMG) {
+#pragma unroll
+    for (int k = 0; k < QPB; ++k) sum[k] += img[(q0 + k) * NT + tid];
+  }
+#pragma unroll
+  for (int k = 0; k < QPB; ++k) {
+    const int q = q0 + k;
+    const int v = q & 15, j = (q >> 4) % TN, i = (q >> 4) / TN;
+    const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    const int n = n0 + wn0 + j * 32 + (lane & 31);
+    if (m < g.M && n < g.N) {
+      const int64_t o = (int64_t)m * g.N + n;
+      if (g.out_f32) g.out_f32[o] = (float)sum[k] * (g.row_scale[(int64_t)m * g.row_stride] * cs);
+      else g.out_i32[o] = sum[k];
     }
   }
 }
