@@ -32,31 +32,45 @@ hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t 
   return hipGetLastError();
 }
 
-// Tile configurations (measured on MI355X).  The 256x256 tile (one workgroup per compute
-// unit, 128x128 per wave) has the best matrix-core duty cycle and the lowest operand
-// traffic per operation, but needs >= 1024 tiles to balance 256 compute units.  Below
-// that the 128x128 tile runs three workgroups per unit, which also overlaps one
-// workgroup's output stores with the others' main loops; INT8 operands (twice the bytes
-// per operation) take 128-byte K stages there.  A GEMM with a small output and a long K
-// (the g_w path) is split along K only as far as needed to give every compute unit a
-// workgroup: each extra slice costs a full int32 image of the output in HBM traffic.
+// Tile configurations.  Three workgroup tiles exist: 128x128 (64x64 per wave, three
+// workgroups per compute unit, so one workgroup's stores overlap the others' main
+// loops, but the INT4 widening costs 6 vector instructions per matrix instruction and
+// the vector pipe becomes the limit), 192x256 and 256x256 (96x128 / 128x128 per wave,
+// one workgroup per unit, half the widening and LDS traffic per matrix instruction, but
+// nothing hides the output stores and a partial last round idles units).  The choice
+// minimises a cost model fitted to measurements on MI355X: rounds over the 256 units
+// x (tile operations / sustained rate of that tile + unhidden store time).  INT8
+// operands (twice the bytes per operation) take 128-byte K stages.  A GEMM with a small
+// output and a long K (the g_w path) is split along K only as far as needed to give
+// every unit a workgroup: each extra slice costs an int32 image of the output in HBM.
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_split) {
+  struct Cand { int bm, bn; double tops; bool hides_stores; };
+  static const Cand cands4[] = {{128, 128, 1900., true}, {192, 256, 2700., false}, {256, 256, 3200., false}};
+  static const Cand cands8[] = {{128, 128, 1000., true}, {256, 256, 2200., false}};
+  const Cand* cands = bits == 4 ? cands4 : cands8;
+  const int ncand = bits == 4 ? 3 : 2;
+  const double K = (double)k_bytes * (bits == 4 ? 2 : 1);
   GemmPlan p;
-  const int64_t t256 = ceil_div(M, 256) * ceil_div(N, 256);
-  const int64_t t128 = ceil_div(M, 128) * ceil_div(N, 128);
   p.split = 1;
   p.partial_bytes = 0;
-  if (t256 >= 1024) {
-    p.bm = p.bn = 256;
-    p.bkb = bits == 4 ? 64 : 128;
-    p.tiles = t256;
-    return p;
+  double best = 1e30;
+  for (int c = 0; c < ncand; ++c) {
+    const int64_t tiles = ceil_div(M, cands[c].bm) * ceil_div(N, cands[c].bn);
+    const double rounds = (double)ceil_div(tiles, 256);
+    const double ops = 2.0 * cands[c].bm * cands[c].bn * K;
+    double t = ops / (cands[c].tops * 1e12 / 256);
+    if (!cands[c].hides_stores) t += 4.0 * cands[c].bm * cands[c].bn / (5.5e12 / 256);
+    t *= rounds;
+    if (t < best) {
+      best = t;
+      p.bm = cands[c].bm;
+      p.bn = cands[c].bn;
+      p.tiles = tiles;
+    }
   }
-  p.bm = p.bn = 128;
   p.bkb = bits == 4 ? 64 : 128;
-  p.tiles = t128;
-  if (allow_split) {
-    int64_t s = 256 / t128;
+  if (allow_split && p.bm == 128) {
+    int64_t s = 256 / p.tiles;
     const int64_t nk = k_bytes / p.bkb;
     if (s > nk / 4) s = nk / 4;   // at least 4 stages per slice
     if (s >= 2) {
@@ -75,7 +89,7 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, hipStream_t s, int gemm_stag
   g.stages_per_split = (int)ceil_div(g.nk_total, g.split);
   g.tiles_m = (int)ceil_div(g.M, BM);
   g.tiles_n = (int)ceil_div(g.N, BN);
-  const size_t lds = 2 * (size_t)(BM + BN) * (BKB + 16);
+  const size_t lds = 2 * (size_t)(BM + BN) * BKB;
   auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
@@ -123,6 +137,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   if (plan.bm == 256)
     return bits == 4 ? launch_tile<256, 256, 64, true>(g, k_bytes, s, gs, rs)
                      : launch_tile<256, 256, 128, false>(g, k_bytes, s, gs, rs);
+  if (plan.bm == 192 && bits == 4) return launch_tile<192, 256, 64, true>(g, k_bytes, s, gs, rs);
   if (plan.bm == 128)
     return bits == 4 ? launch_tile<128, 128, 64, true>(g, k_bytes, s, gs, rs)
                      : launch_tile<128, 128, 128, false>(g, k_bytes, s, gs, rs);

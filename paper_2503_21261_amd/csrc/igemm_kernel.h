@@ -97,7 +97,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int LP = BKB + 16;
+  constexpr int LP = BKB;               // LDS row pitch; 16-byte chunks are XOR-swizzled (below)
   constexpr int TPR = BKB / 16;
   constexpr int RPP = NT / TPR;
   constexpr int PA = BM / RPP, PB = BN / RPP;
@@ -119,13 +119,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   if (k_end > g.nk_total) k_end = g.nk_total;
   const int nk = k_end - k_begin;
   if (g.out_f32) {  // visible to every wave after the barrier that follows the first LDS stage
-    const float cs = (*g.col_scale) * g.inv_n;
+    // INT4 accumulators carry an exact factor 256 (a power of two: folding it into the
+    // row factor gives the same fp32 result as shifting the integer first)
+    const float cs = (*g.col_scale) * g.inv_n * (INT4 ? 1.0f / 256.0f : 1.0f);
     for (int i = tid; i < BM; i += NT)
       s_rowfac[i] = m0 + i < g.M ? g.row_scale[(int64_t)(m0 + i) * g.row_stride] * cs : 0.0f;
   }
   __syncthreads();
 
+  // LDS layout: row r of a tile holds its BKB bytes as 16-byte chunks, chunk c stored at
+  // position c ^ f(r), f(r) = (r >> 1) & 3 for 64-byte rows, r & 7 for 128-byte rows.  Any
+  // 8 consecutive rows reading the same chunk, and any row writing its chunks, then hit 32
+  // distinct banks: no padding, no conflicts.  f only uses row bits 0-2, so tile-row offsets
+  // that are multiples of 8 keep a thread's swizzle constant.
+  auto swz = [](int r) { return TPR == 4 ? (r >> 1) & 3 : r & 7; };
   const int lr = tid / TPR, lseg = (tid % TPR) * 16;
+  const int st_off = lr * LP + 16 * ((tid % TPR) ^ swz(lr));
   const uint8_t* a_src[PA];
   const uint8_t* b_src[PB];
 #pragma unroll
@@ -151,10 +160,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   auto store_stage = [&](int buf) {
 #pragma unroll
     for (int p = 0; p < PA; ++p)
-      *reinterpret_cast<v4i*>(&As[buf * BM * LP + (lr + RPP * p) * LP + lseg]) = ra[p];
+      *reinterpret_cast<v4i*>(&As[buf * BM * LP + RPP * p * LP + st_off]) = ra[p];
 #pragma unroll
     for (int p = 0; p < PB; ++p)
-      *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + (lr + RPP * p) * LP + lseg]) = rb[p];
+      *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + RPP * p * LP + st_off]) = rb[p];
   };
 
   v16i acc[TM][TN];
@@ -165,8 +174,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-  const int a_off = (wm0 + (lane & 31)) * LP + (lane >> 5) * 16;
-  const int b_off = (wn0 + (lane & 31)) * LP + (lane >> 5) * 16;
+  int a_off[KS], b_off[KS];  // fragment of K slice ks: chunk 2*ks + lane/32 of row lane%32
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int pos = 16 * ((2 * ks + (lane >> 5)) ^ swz(lane & 31));
+    a_off[ks] = (wm0 + (lane & 31)) * LP + pos;
+    b_off[ks] = (wn0 + (lane & 31)) * LP + pos;
+  }
   v4i fa[TM], fb[TN];  // raw 16-byte fragments in flight (INT4 only)
   // One K slice = NM matrix instructions; everything else the slice has to issue is
   // cut into "events" that are emitted, in a fixed order, between those instructions:
@@ -183,8 +197,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   auto read_one = [&](Operands<TM, TN, INT4>& un, int buf, int ks, auto fc) {
     constexpr int f = decltype(fc)::value;
     v4i val;
-    if constexpr (f < TM) val = *reinterpret_cast<const v4i*>(&As[buf * BM * LP + a_off + f * 32 * LP + ks * 32]);
-    else val = *reinterpret_cast<const v4i*>(&Bs[buf * BN * LP + b_off + (f - TM) * 32 * LP + ks * 32]);
+    if constexpr (f < TM) val = *reinterpret_cast<const v4i*>(&As[buf * BM * LP + a_off[ks] + f * 32 * LP]);
+    else val = *reinterpret_cast<const v4i*>(&Bs[buf * BN * LP + b_off[ks] + (f - TM) * 32 * LP]);
     if constexpr (INT4) {
       if constexpr (f < TM) fa[f] = val; else fb[f - TM] = val;
     } else {
@@ -211,8 +225,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   };
   auto store_one = [&](int buf, auto pc) {
     constexpr int p = decltype(pc)::value;
-    if constexpr (p < PA) *reinterpret_cast<v4i*>(&As[buf * BM * LP + (lr + RPP * p) * LP + lseg]) = ra[p];
-    else *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + (lr + RPP * (p - PA)) * LP + lseg]) = rb[p - PA];
+    if constexpr (p < PA) *reinterpret_cast<v4i*>(&As[buf * BM * LP + RPP * p * LP + st_off]) = ra[p];
+    else *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + RPP * (p - PA) * LP + st_off]) = rb[p - PA];
   };
   auto load_one = [&](int64_t off, auto pc) {
     constexpr int p = decltype(pc)::value;
@@ -289,28 +303,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   // column lane%32, so each register is stored as 32-float (128-byte) row segments.
   // The row factors come from LDS (filled before the main loop): a global load per row
   // here could not be hoisted above the output stores and would serialise on L2 latency.
+  // Offsets within the tile are 32-bit on top of a uniform base pointer.
+  const int nl0 = wn0 + (lane & 31);
+  if (g.out_f32) {
+    float* obase = g.out_f32 + ((int64_t)m0 * g.N + n0);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      const int m = m0 + ml;
-      if (m >= g.M) continue;
-      const float rs = s_rowfac[ml];
+      for (int v = 0; v < 16; ++v) {
+        const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m0 + ml >= g.M) continue;
+        const float rs = s_rowfac[ml];
+        const int row_off = ml * g.N + nl0;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn0 + j * 32 + (lane & 31);
-        if (n >= g.N) continue;
-        int c = acc[i][j][v];
-        if constexpr (INT4) c >>= 8;
-        const int64_t o = (int64_t)m * g.N + n;
-        if (g.out_f32) g.out_f32[o] = (float)c * rs;
-        else g.out_i32[o] = c;
+        for (int j = 0; j < TN; ++j)
+          if (n0 + nl0 + j * 32 < g.N) obase[row_off + j * 32] = (float)acc[i][j][v] * rs;
+      }
+    }
+  } else {
+    int32_t* obase = g.out_i32 + ((int64_t)m0 * g.N + n0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (m0 + ml >= g.M) continue;
+        const int row_off = ml * g.N + nl0;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          if (n0 + nl0 + j * 32 < g.N) obase[row_off + j * 32] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
       }
     }
   }
 }
-
 
 // Second half of a split-K GEMM: out[m][n] = epilogue(sum over slices of the register
 // images the GEMM left), slices added in order (exact in int32).  One workgroup handles
