@@ -37,6 +37,8 @@ def stage_model(L, O, I, n, r, gx_bits, per_token):
         "gy_row_quant2": dict(bound="hbm", bytes=4 * L * O + cb * L * O),
         "gyT_col_absmax": dict(bound="hbm", bytes=4 * L * O),
         "gyT_col_quant": dict(bound="hbm", bytes=4 * L * O + Lr * O),
+        "gy_fused_absmax": dict(bound="hbm", bytes=4 * L * O + (4 * L * ((O + 127) // 128) if per_token else 0)),
+        "gy_fused_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + Lr * O + 4 * L),
         "gx_igemm": dict(bound="mfma", ops=2 * L * O * I, bytes=cb * (L * O + I * O) + 4 * L * I),
         "gw_igemm": dict(bound="mfma", ops=2 * O * I * Lr, bytes=Lr * (O + I) + 4 * O * I),
     }
@@ -84,6 +86,10 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="repeat the oracle on the sample until about this much CPU wall time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-call", action="store_true",
+                    help="run the backward as hot_linear_backward (two shared passes over g_y, "
+                         "vector-ALU-bound) instead of hot_linear_backward_gx + "
+                         "hot_linear_backward_gw (three HBM-bound passes, faster on MI355X)")
     ap.add_argument("--probe-peaks", action="store_true",
                     help="instead of the workload, time plain HBM read/write and a register-only "
                          "int8 matrix loop, and print them as JSON")
@@ -121,8 +127,11 @@ def main() -> int:
 
     def step():
         hot.hot_compress_activation(cfg, x, act, ws, stream=stream)
-        hot.hot_linear_backward_gx(cfg, gy, w, q, gx, ws, stream=stream)
-        hot.hot_linear_backward_gw(cfg, gy, act, I, gw, ws, stream=stream)
+        if not args.one_call:
+            hot.hot_linear_backward_gx(cfg, gy, w, q, gx, ws, stream=stream)
+            hot.hot_linear_backward_gw(cfg, gy, act, I, gw, ws, stream=stream)
+        else:
+            hot.hot_linear_backward(cfg, gy, w, act, q, gx, gw, ws, stream=stream)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(gy)
@@ -202,7 +211,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
                    "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
-                   "step": "compress_activation + linear_backward_gx + linear_backward_gw"},
+                   "step": "compress_activation + linear_backward_gx + linear_backward_gw" if not args.one_call
+                   else "compress_activation + linear_backward (g_x and g_w in one call)"},
         "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
     }

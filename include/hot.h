@@ -101,6 +101,24 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
                                   float* g_x, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Frozen weights (Sec. 5.3: with LoRA-style fine-tuning the base weights stay fixed and
+ * only g_x is needed): quantise H.w once, reuse it every step.
+ * hot_weight_buffer_bytes: a 256-byte header holding the scale, then I rows of O codes
+ * (gx_bits each, row pitch rounded up to 128 bytes); 0 for an invalid config or shape.
+ * hot_quantize_weight: w device [O x I] (in) -> wq_buf device (out); ws: the first 17 KB.
+ * hot_linear_backward_gx_cached: hot_linear_backward_gx with the weight operand taken
+ * from wq_buf (same cfg, O, I); same g_x bit for bit; ws may be smaller by the weight
+ * codes.
+ */
+size_t hot_weight_buffer_bytes(const hot_config* cfg, int64_t O, int64_t I);
+hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O, int64_t I,
+                               void* wq_buf, void* ws, size_t ws_bytes, void* stream);
+hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
+                                         const void* wq_buf, int64_t L, int64_t O, int64_t I,
+                                         hot_quantizer gy_quantizer, float* g_x, void* ws,
+                                         size_t ws_bytes, void* stream);
+
+/*
  * Weight-gradient path, Sec. 5.2 (Eq. 5 with INT8 operands):
  *   g_w = dequant( Q(HLA(g_y))^T . x_hat ),  HLA along the token index L.
  * g_y: device [L x O] (in); act_buf: what hot_compress_activation wrote for the
@@ -109,6 +127,20 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
 hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
                                   int64_t L, int64_t O, int64_t I, float* g_w, void* ws,
                                   size_t ws_bytes, void* stream);
+
+/*
+ * Both gradients of one layer in one call (Sec. 5.1 and 5.2 on the same g_y): the same
+ * g_x and g_w, bit for bit, as hot_linear_backward_gx followed by
+ * hot_linear_backward_gw, but the two quantised views of g_y (rotated along O, and
+ * HLA-compressed along L) come out of shared reads of g_y: two passes over it instead
+ * of three (four with a per-tensor g_y scale).  Block sizes 16 and 32 take the shared
+ * passes; block size 64 runs the two separate paths one after the other.
+ * Arguments as for the two separate calls.  Requires O % n == 0 and L % n == 0.
+ */
+hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const float* w,
+                               const void* act_buf, int64_t L, int64_t O, int64_t I,
+                               hot_quantizer gy_quantizer, float* g_x, float* g_w, void* ws,
+                               size_t ws_bytes, void* stream);
 
 /*
  * Layer-wise Quantizer Selection, Sec. 5.2.2, for one layer's calibration g_y:
@@ -128,6 +160,10 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
 hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_buf, int64_t L,
                                        int64_t I, int8_t* codes, float* scale, void* stream);
 
+/* Quantised weights as row-major codes [O x I] (one code per byte) and their scale [1]. */
+hot_status hot_debug_unpack_weight(const hot_config* cfg, const void* wq_buf, int64_t O, int64_t I,
+                                   int8_t* codes, float* scale, void* stream);
+
 /* Operands left in `ws` by the last hot_linear_backward_gx with these arguments:
  * codes of the rotated g_y [L x O] and w [O x I] (row-major, one code per byte),
  * scales of g_y ([L] per token, [1] per tensor) and of w [1], and the int32
@@ -145,10 +181,26 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
                                  int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
                                  float* gy_scale, int32_t* acc, void* stream);
 
+/* Operands left in `ws` by the last hot_linear_backward (block size 16 or 32): the
+ * outputs of both views above.  Any output may be NULL. */
+hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+                                    int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
+                                    int8_t* gy_codes, float* gy_scales, int8_t* w_codes,
+                                    float* w_scale, int32_t* acc_gx, int8_t* gyT_codes,
+                                    float* gyT_scale, int32_t* acc_gw, void* stream);
+
+/* Tensors small enough to stay in the register files of the resident workgroups (x and
+ * w of the ViT-sized layers) are transformed and quantised by a single-pass kernel whose
+ * workgroups exchange their abs-max through the workspace and wait for each other at most
+ * `us` microseconds (default 200) before computing what is missing themselves; results
+ * do not depend on the value.  us = 0: never wait (exercises the self-computed path);
+ * us < 0: always use the two-pass kernels.  Process-wide setting. */
+hot_status hot_debug_set_exchange_wait_us(int us);
+
 /* ---- stage timing for benchmarks (off by default) ---- */
 
 /* Kernel roles timed separately; hot_debug_stage_name() gives their names. */
-#define HOT_NUM_STAGES 13
+#define HOT_NUM_STAGES 15
 
 /* From this call on, every kernel the library launches is bracketed by two HIP
  * events recorded on its stream.  Host-side state only; not thread-safe against

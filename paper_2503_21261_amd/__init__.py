@@ -25,12 +25,13 @@ HOT_ROUND_NEAREST_EVEN, HOT_ROUND_PSEUDO_STOCHASTIC = 0, 1
 
 EXPORTS = (
     "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
-    "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
-    "hot_select_quantizer", "hot_debug_unpack_activation", "hot_debug_gx_operands",
-    "hot_debug_gw_operands", "hot_debug_profile_begin", "hot_debug_profile_end",
+    "hot_weight_buffer_bytes", "hot_quantize_weight", "hot_linear_backward_gx_cached",
+    "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
+    "hot_linear_backward", "hot_select_quantizer", "hot_debug_unpack_activation",
+    "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us", "hot_debug_profile_begin", "hot_debug_profile_end",
     "hot_debug_stage_name", "hot_debug_probe",
 )
-HOT_NUM_STAGES = 13
+HOT_NUM_STAGES = 15
 
 
 class hot_config(C.Structure):
@@ -70,15 +71,23 @@ def lib() -> C.CDLL:
         l.hot_compress_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, sz, vp]
         l.hot_linear_backward_gx.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
         l.hot_linear_backward_gw.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, sz, vp]
+        l.hot_linear_backward.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, sz, vp]
         l.hot_select_quantizer.argtypes = [cfgp, vp, i64, i64, C.POINTER(C.c_int),
                                            C.POINTER(C.c_double), C.POINTER(C.c_double), vp, sz, vp]
         l.hot_debug_unpack_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
         l.hot_debug_gx_operands.argtypes = [cfgp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp, vp]
         l.hot_debug_gw_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        l.hot_debug_fused_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int] + [vp] * 9
+        l.hot_debug_set_exchange_wait_us.argtypes = [C.c_int]
         l.hot_debug_profile_begin.argtypes = []
         l.hot_debug_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int64)]
         l.hot_debug_probe.argtypes = [C.c_int, vp, sz, C.c_int, vp]
-        for name in EXPORTS[4:]:
+        l.hot_weight_buffer_bytes.argtypes = [cfgp, i64, i64]
+        l.hot_weight_buffer_bytes.restype = sz
+        l.hot_quantize_weight.argtypes = [cfgp, vp, i64, i64, vp, vp, sz, vp]
+        l.hot_linear_backward_gx_cached.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+        l.hot_debug_unpack_weight.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
+        for name in EXPORTS[5:]:
             if name != "hot_debug_stage_name":
                 getattr(l, name).restype = C.c_int
         l.hot_debug_stage_name.argtypes = [C.c_int]
@@ -158,6 +167,49 @@ def alloc_act_buffer(cfg: Config, L: int, I: int, device="cuda") -> torch.Tensor
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def hot_weight_buffer_bytes(cfg: Config, O: int, I: int) -> int:
+    return int(lib().hot_weight_buffer_bytes(C.byref(cfg.c()), O, I))
+
+
+def alloc_weight_buffer(cfg: Config, O: int, I: int, device="cuda") -> torch.Tensor:
+    n = hot_weight_buffer_bytes(cfg, O, I)
+    if n == 0:
+        raise HotError(HOT_ERR_SHAPE, "hot_weight_buffer_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def hot_quantize_weight(cfg: Config, w: torch.Tensor, wq_buf: torch.Tensor, ws: torch.Tensor,
+                        stream=None) -> torch.Tensor:
+    O, I = w.shape
+    _dev_f32(w, (O, I), "w")
+    st = lib().hot_quantize_weight(C.byref(cfg.c()), _ptr(w), O, I, _ptr(wq_buf), _ptr(ws),
+                                   ws.numel(), _stream(stream))
+    _check(st, "hot_quantize_weight")
+    return wq_buf
+
+
+def hot_linear_backward_gx_cached(cfg: Config, g_y: torch.Tensor, wq_buf: torch.Tensor, I: int,
+                                  gy_quantizer: int, g_x: torch.Tensor, ws: torch.Tensor,
+                                  stream=None) -> torch.Tensor:
+    L, O = g_y.shape
+    _dev_f32(g_y, (L, O), "g_y"); _dev_f32(g_x, (L, I), "g_x")
+    st = lib().hot_linear_backward_gx_cached(C.byref(cfg.c()), _ptr(g_y), _ptr(wq_buf), L, O, I,
+                                             int(gy_quantizer), _ptr(g_x), _ptr(ws), ws.numel(),
+                                             _stream(stream))
+    _check(st, "hot_linear_backward_gx_cached")
+    return g_x
+
+
+def hot_debug_unpack_weight(cfg: Config, wq_buf: torch.Tensor, O: int, I: int, stream=None):
+    """Returns (codes int8 [O, I], scale float32 [1]) on the device."""
+    codes = torch.empty((O, I), dtype=torch.int8, device=wq_buf.device)
+    scale = torch.empty(1, dtype=torch.float32, device=wq_buf.device)
+    st = lib().hot_debug_unpack_weight(C.byref(cfg.c()), _ptr(wq_buf), O, I, _ptr(codes),
+                                       _ptr(scale), _stream(stream))
+    _check(st, "hot_debug_unpack_weight")
+    return codes, scale
+
+
 def hot_compress_activation(cfg: Config, x: torch.Tensor, act_buf: torch.Tensor,
                             ws: torch.Tensor, stream=None) -> torch.Tensor:
     L, I = x.shape
@@ -188,6 +240,20 @@ def hot_linear_backward_gw(cfg: Config, g_y: torch.Tensor, act_buf: torch.Tensor
                                       _ptr(g_w), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "hot_linear_backward_gw")
     return g_w
+
+
+def hot_linear_backward(cfg: Config, g_y: torch.Tensor, w: torch.Tensor, act_buf: torch.Tensor,
+                        gy_quantizer: int, g_x: torch.Tensor, g_w: torch.Tensor, ws: torch.Tensor,
+                        stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    L, O = g_y.shape
+    I = w.shape[1]
+    _dev_f32(g_y, (L, O), "g_y"); _dev_f32(w, (O, I), "w")
+    _dev_f32(g_x, (L, I), "g_x"); _dev_f32(g_w, (O, I), "g_w")
+    st = lib().hot_linear_backward(C.byref(cfg.c()), _ptr(g_y), _ptr(w), _ptr(act_buf), L, O, I,
+                                   int(gy_quantizer), _ptr(g_x), _ptr(g_w), _ptr(ws), ws.numel(),
+                                   _stream(stream))
+    _check(st, "hot_linear_backward")
+    return g_x, g_w
 
 
 def hot_select_quantizer(cfg: Config, g_y: torch.Tensor, ws: torch.Tensor,
@@ -241,6 +307,31 @@ def hot_debug_gw_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, 
                                      _ptr(sg), _ptr(acc), _stream(stream))
     _check(st, "hot_debug_gw_operands")
     return dict(qg=qg, sg=sg, acc=acc)
+
+
+def hot_debug_fused_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, L: int, O: int,
+                             I: int, gy_quantizer: int, want_acc: bool = True, stream=None):
+    """Operands of the last hot_linear_backward: dict(qg, sg, qw, sw, acc_gx, qgh, sgh, acc_gw)."""
+    dev = ws.device
+    Lr = L // cfg.block * cfg.keep
+    qg = torch.empty((L, O), dtype=torch.int8, device=dev)
+    sg = torch.empty(L if gy_quantizer == HOT_Q_PER_TOKEN else 1, dtype=torch.float32, device=dev)
+    qw = torch.empty((O, I), dtype=torch.int8, device=dev)
+    sw = torch.empty(1, dtype=torch.float32, device=dev)
+    qgh = torch.empty((Lr, O), dtype=torch.int8, device=dev)
+    sgh = torch.empty(1, dtype=torch.float32, device=dev)
+    acc_gx = torch.empty((L, I), dtype=torch.int32, device=dev) if want_acc else None
+    acc_gw = torch.empty((O, I), dtype=torch.int32, device=dev) if want_acc else None
+    st = lib().hot_debug_fused_operands(C.byref(cfg.c()), _ptr(ws), _ptr(act_buf), L, O, I,
+                                        int(gy_quantizer), _ptr(qg), _ptr(sg), _ptr(qw), _ptr(sw),
+                                        _ptr(acc_gx), _ptr(qgh), _ptr(sgh), _ptr(acc_gw),
+                                        _stream(stream))
+    _check(st, "hot_debug_fused_operands")
+    return dict(qg=qg, sg=sg, qw=qw, sw=sw, acc_gx=acc_gx, qgh=qgh, sgh=sgh, acc_gw=acc_gw)
+
+
+def hot_debug_set_exchange_wait_us(us: int) -> None:
+    _check(lib().hot_debug_set_exchange_wait_us(int(us)), "hot_debug_set_exchange_wait_us")
 
 
 def hot_debug_profile_begin() -> None:

@@ -90,6 +90,26 @@ SelLayout sel_layout(const Config&, int64_t L, int64_t) {
   return s;
 }
 
+FusedLayout fused_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
+  FusedLayout f;
+  f.gx = gx_layout(c, L, O, I);
+  f.gw = gw_layout(c, L, O, I);
+  f.s_gh = 16;
+  f.rowpart = (size_t)round_up((int64_t)f.gx.total, 256);
+  f.qgh = f.rowpart + (size_t)round_up(gy_fused_tiles_x(O) * L * 4, 256);
+  f.partial = f.qgh + (size_t)round_up(O * f.gw.pitch, 256);
+  f.total = f.partial + f.gw.plan.partial_bytes;
+  return f;
+}
+
+WeightLayout weight_layout(const Config& c, int64_t O, int64_t I) {
+  WeightLayout w;
+  w.pitch = round_up(O * c.gx_bits / 8, kPitchAlign);
+  w.codes = kHeaderBytes;
+  w.total = w.codes + (size_t)(I * w.pitch);
+  return w;
+}
+
 ActLayout act_layout(const Config& c, int64_t L, int64_t I) {
   ActLayout a;
   a.Lr = L / c.n * c.r;
@@ -177,6 +197,10 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
   if (tok_shape_ok(c, L, O) && tok_shape_ok(c, L, I)) {
     const size_t a = gw_layout(c, L, O, I).total;
     need = a > need ? a : need;
+    if (gx_shape_ok(c, L, O, I) && gy_fused_supported(c)) {
+      const size_t b = fused_layout(c, L, O, I).total;
+      need = b > need ? b : need;
+    }
   }
   return need;
 }
@@ -198,6 +222,54 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   return HOT_OK;
 }
 
+size_t hot_weight_buffer_bytes(const hot_config* cfg, int64_t O, int64_t I) {
+  Config c;
+  if (resolve_config(cfg, &c) != HOT_OK || !gx_shape_ok(c, 1, O, I)) return 0;
+  return weight_layout(c, O, I).total;
+}
+
+hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O, int64_t I,
+                               void* wq_buf, void* ws, size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!w || !wq_buf || !ws || !aligned16(w) || !aligned16(wq_buf) || !aligned16(ws)) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, 1, O, I)) return HOT_ERR_SHAPE;
+  if (ws_bytes < (size_t)kWsPrefix) return HOT_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const WeightLayout wl = weight_layout(c, O, I);
+  uint8_t* base = (uint8_t*)wq_buf;
+  float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, base + wl.codes,
+                           wl.pitch, (float*)base, partials, s, kStWAbsmax, kStWQuant));
+  return HOT_OK;
+}
+
+namespace {
+
+// The g_x path given quantised weights (codes [I x pitch], scale): rotate and quantise
+// g_y, multiply, dequantise.
+hot_status run_gx(const Config& c, const float* g_y, const uint8_t* qw, const float* s_w, int64_t L,
+                  int64_t O, int64_t I, hot_quantizer gy_quantizer, float* g_x, uint8_t* base,
+                  const GxLayout& g, hipStream_t s) {
+  float* part_g = (float*)(base + kHeaderBytes + kPartialBytes);
+  float* s_g = (float*)(base + g.sg);
+  uint8_t* qg = base + g.qg;
+  int npart = 0;
+  if (gy_quantizer == HOT_Q_PER_TOKEN) {
+    HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, part_g, &npart, s));
+  } else {
+    HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
+    HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
+  }
+  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits,
+                       plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
+                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
+  return HOT_OK;
+}
+
+}  // namespace
+
 hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const float* w,
                                   int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
                                   float* g_x, void* ws, size_t ws_bytes, void* stream) {
@@ -214,27 +286,31 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   uint8_t* base = (uint8_t*)ws;
   float* s_w = (float*)(base + g.scalars);
   float* part_w = (float*)(base + kHeaderBytes);
-  float* part_g = (float*)(base + kHeaderBytes + kPartialBytes);
-  float* s_g = (float*)(base + g.sg);
-  uint8_t* qg = base + g.qg;
   uint8_t* qw = base + g.qw;
-  const KeepMap ident = identity_map(c.n);
-
   // H.w along O, one scale, written as [I x O] code rows
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, ident, true, c.gx_bits, qw, g.pitch, s_w, part_w, s,
-                           kStWAbsmax, kStWQuant));
-  // g_y.H^T along O
-  int npart = 0;
-  if (gy_quantizer == HOT_Q_PER_TOKEN) {
-    HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, part_g, &npart, s));
-  } else {
-    HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
-    HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
-  }
-  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits,
-                       plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
-                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
-  return HOT_OK;
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
+                           part_w, s, kStWAbsmax, kStWQuant));
+  return run_gx(c, g_y, qw, s_w, L, O, I, gy_quantizer, g_x, base, g, s);
+}
+
+hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
+                                         const void* wq_buf, int64_t L, int64_t O, int64_t I,
+                                         hot_quantizer gy_quantizer, float* g_x, void* ws,
+                                         size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !wq_buf || !g_x || !ws || !aligned16(g_y) || !aligned16(wq_buf) || !aligned16(g_x) ||
+      !aligned16(ws))
+    return HOT_ERR_ARG;
+  if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
+  const GxLayout g = gx_layout(c, L, O, I);
+  if (ws_bytes < g.qw) return HOT_ERR_WORKSPACE;   // the weight-code region of ws is not needed
+  const WeightLayout wl = weight_layout(c, O, I);
+  const uint8_t* wb = (const uint8_t*)wq_buf;
+  return run_gx(c, g_y, wb + wl.codes, (const float*)wb, L, O, I, gy_quantizer, g_x, (uint8_t*)ws, g,
+                (hipStream_t)stream);
 }
 
 hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
@@ -263,6 +339,53 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
                            kStGyTAbsmax, kStGyTQuant));
   HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.plan, partial,
                        nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
+  return HOT_OK;
+}
+
+hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const float* w,
+                               const void* act_buf, int64_t L, int64_t O, int64_t I,
+                               hot_quantizer gy_quantizer, float* g_x, float* g_w, void* ws,
+                               size_t ws_bytes, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !w || !act_buf || !g_x || !g_w || !ws || !aligned16(g_y) || !aligned16(w) ||
+      !aligned16(act_buf) || !aligned16(g_x) || !aligned16(g_w) || !aligned16(ws))
+    return HOT_ERR_ARG;
+  if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  if (!gy_fused_supported(c)) {
+    st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
+    if (st != HOT_OK) return st;
+    return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
+  }
+  const FusedLayout f = fused_layout(c, L, O, I);
+  if (ws_bytes < f.total) return HOT_ERR_WORKSPACE;
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)ws;
+  float* s_w = (float*)(base + f.gx.scalars);
+  float* s_gh = (float*)(base + f.s_gh);
+  float* part_a = (float*)(base + kHeaderBytes);
+  float* part_b = (float*)(base + kHeaderBytes + kPartialBytes);
+  float* s_g = (float*)(base + f.gx.sg);
+  uint8_t* qg = base + f.gx.qg;
+  uint8_t* qw = base + f.gx.qw;
+  uint8_t* qgh = base + f.qgh;
+  int32_t* partial = f.gw.plan.split > 1 ? (int32_t*)(base + f.partial) : nullptr;
+  const uint8_t* abase = (const uint8_t*)act_buf;
+  const bool per_token = gy_quantizer == HOT_Q_PER_TOKEN;
+
+  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, f.gx.pitch, s_w,
+                           part_a, s, kStWAbsmax, kStWQuant));
+  HOT_TRY(launch_gy_fused(g_y, L, O, c, per_token, qg, f.gx.pitch, s_g, qgh, f.gw.pitch, s_gh, part_a,
+                          part_b, (float*)(base + f.rowpart), s, kStGyFusedAbsmax, kStGyFusedQuant));
+  HOT_TRY(launch_igemm(qg, qw, L, I, f.gx.pitch, f.gx.pitch, c.gx_bits,
+                       plan_gemm(L, I, f.gx.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
+                       per_token ? 1 : 0, s_w, c.n, s, kStGxGemm));
+  HOT_TRY(launch_igemm(qgh, abase + a.codes, O, I, f.gw.pitch, f.gw.pitch, c.gw_bits, f.gw.plan,
+                       partial, nullptr, g_w, s_gh, 0, (const float*)abase, c.n, s, kStGwGemm,
+                       kStGwReduce));
   return HOT_OK;
 }
 
@@ -314,6 +437,26 @@ hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_bu
   return HOT_OK;
 }
 
+hot_status hot_debug_set_exchange_wait_us(int us) {
+  set_exchange_wait_us(us);
+  return HOT_OK;
+}
+
+hot_status hot_debug_unpack_weight(const hot_config* cfg, const void* wq_buf, int64_t O, int64_t I,
+                                   int8_t* codes, float* scale, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!wq_buf) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, 1, O, I)) return HOT_ERR_SHAPE;
+  const WeightLayout wl = weight_layout(c, O, I);
+  hipStream_t s = (hipStream_t)stream;
+  const uint8_t* base = (const uint8_t*)wq_buf;
+  if (codes) HOT_TRY(launch_unpack(base + wl.codes, I, O, wl.pitch, c.gx_bits, 1, codes, s));
+  if (scale) HOT_TRY(hipMemcpyAsync(scale, base, 4, hipMemcpyDeviceToDevice, s));
+  return HOT_OK;
+}
+
 hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t L, int64_t O,
                                  int64_t I, hot_quantizer gy_quantizer, int8_t* gy_codes,
                                  float* gy_scales, int8_t* w_codes, float* w_scale, int32_t* acc,
@@ -357,6 +500,33 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
     HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch, 8,
                          plan_gemm(O, I, g.pitch, 8, false), nullptr, acc, nullptr, nullptr, 0,
                          nullptr, c.n, s));
+  return HOT_OK;
+}
+
+hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+                                    int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
+                                    int8_t* gy_codes, float* gy_scales, int8_t* w_codes,
+                                    float* w_scale, int32_t* acc_gx, int8_t* gyT_codes,
+                                    float* gyT_scale, int32_t* acc_gw, void* stream) {
+  Config c;
+  hot_status st = resolve_config(cfg, &c);
+  if (st != HOT_OK) return st;
+  if (!ws || (acc_gw && !act_buf)) return HOT_ERR_ARG;
+  if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  if (!gy_fused_supported(c)) return HOT_ERR_UNIMPLEMENTED;
+  st = hot_debug_gx_operands(cfg, ws, L, O, I, gy_quantizer, gy_codes, gy_scales, w_codes, w_scale,
+                             acc_gx, stream);
+  if (st != HOT_OK) return st;
+  const FusedLayout f = fused_layout(c, L, O, I);
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  const uint8_t* base = (const uint8_t*)ws;
+  if (gyT_codes) HOT_TRY(launch_unpack(base + f.qgh, O, f.gw.Lr, f.gw.pitch, 8, 1, gyT_codes, s));
+  if (gyT_scale) HOT_TRY(hipMemcpyAsync(gyT_scale, base + f.s_gh, 4, hipMemcpyDeviceToDevice, s));
+  if (acc_gw)
+    HOT_TRY(launch_igemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, f.gw.pitch,
+                         8, plan_gemm(O, I, f.gw.pitch, 8, false), nullptr, acc_gw, nullptr, nullptr,
+                         0, nullptr, c.n, s));
   return HOT_OK;
 }
 

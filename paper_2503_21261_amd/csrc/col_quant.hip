@@ -1,8 +1,26 @@
 // Launch plan and launcher of the column-direction transform/quantise kernels
 // (col_quant_kernel.h).
+#include <atomic>
+#include <chrono>
+
 #include "col_quant_kernel.h"
 
 namespace hot {
+
+namespace {
+// Microseconds a single-pass workgroup waits for the other workgroups' maxima before it
+// computes the missing ones itself; < 0 disables the single-pass kernels.
+std::atomic<int> g_exchange_wait_us{200};
+
+// Launch tags: any sequence that does not repeat within the lifetime of stale slot
+// contents; seeded from the clock so that leftovers of an earlier process differ too.
+uint32_t next_tag() {
+  static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() | 1u};
+  return tag.fetch_add(1, std::memory_order_relaxed);
+}
+}  // namespace
+
+void set_exchange_wait_us(int us) { g_exchange_wait_us.store(us); }
 
 ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity) {
   ColPlan p;
@@ -31,6 +49,25 @@ ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_defa
   while (tiles(p.vec_q, p.kbw_q) < 512 && p.kbw_q > 1) p.kbw_q /= 2;
   p.tiles_q = tiles(p.vec_q, p.kbw_q);
   p.lds_q = (size_t)(64 * p.vec_q) * (4 * p.kbw_q * bpb + 4);
+  // Single pass: the smallest number of blocks per wave (most workgroups, most loads in
+  // flight) whose grid stays within what is resident at once; the launcher checks the
+  // kernel's real occupancy.  One column per lane (two for n = 16), at most 96 block
+  // values per lane.
+  p.kb_one = 0;
+  p.tiles_one = 0;
+  p.lds_one = 0;
+  const int vec1 = onepass_vec(n);
+  if (C % vec1 == 0) {
+    for (int kb = 1; kb <= 3 && kb * vec1 * n <= 96; ++kb) {
+      const int64_t t = tiles(vec1, kb);
+      if (t <= 512) {
+        p.kb_one = kb;
+        p.tiles_one = t;
+        p.lds_one = (size_t)(64 * vec1) * (4 * kb * bpb + 4);
+        break;
+      }
+    }
+  }
   return p;
 }
 
@@ -62,8 +99,54 @@ hipError_t launch_quant(const ColArgs& a, const ColPlan& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Single-pass launch; *done = false (and nothing launched) when the grid would not be
+// resident all at once.
+template <int N, int KIND, int KB>
+hipError_t launch_onepass_kb(const ColArgs& a, const ColPlan& p, hipStream_t s, int sq, bool* done) {
+  constexpr int VEC = onepass_vec(N);
+  auto kern = col_quant_onepass_kernel<N, VEC, KIND, KB>;
+  static int per_cu = -1, cus = 0;   // per instantiation
+  if (per_cu < 0) {
+    int dev = 0, nb = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    // LDS of the largest tile this instantiation can be given (bpb <= N)
+    if (e == hipSuccess)
+      e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 256, (size_t)(64 * VEC) * (4 * KB * N + 4));
+    if (e != hipSuccess) return e;
+    per_cu = nb;
+  }
+  if (p.tiles_one > (int64_t)per_cu * cus) return hipSuccess;
+  const int wait_us = g_exchange_wait_us.load();
+  stage_begin(sq, s);
+  kern<<<dim3((unsigned)p.tiles_one), dim3(256), p.lds_one, s>>>(
+      a.x, a.R, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
+      next_tag(), (long long)wait_us * 100, a.codes, a.pitch, a.scale);
+  stage_end(sq, s);
+  *done = true;
+  return hipGetLastError();
+}
+
+template <int N, int KIND>
+hipError_t launch_onepass(const ColArgs& a, const ColPlan& p, hipStream_t s, int sq, bool* done) {
+  constexpr int VEC = onepass_vec(N);
+  if (p.kb_one == 1) return launch_onepass_kb<N, KIND, 1>(a, p, s, sq, done);
+  if constexpr (2 * VEC * N <= 96) {
+    if (p.kb_one == 2) return launch_onepass_kb<N, KIND, 2>(a, p, s, sq, done);
+  }
+  if constexpr (3 * VEC * N <= 96) {
+    if (p.kb_one == 3) return launch_onepass_kb<N, KIND, 3>(a, p, s, sq, done);
+  }
+  return hipSuccess;
+}
+
 template <int N, int KIND>
 hipError_t launch_nk(const ColArgs& a, const ColPlan& p, hipStream_t s, int sa, int sq) {
+  if (p.kb_one > 0 && g_exchange_wait_us.load() >= 0) {
+    bool done = false;
+    const hipError_t e1 = launch_onepass<N, KIND>(a, p, s, sq, &done);
+    if (e1 != hipSuccess || done) return e1;
+  }
   hipError_t e = hipErrorInvalidValue;
   stage_begin(sa, s);
   if constexpr (N < 64) {

@@ -68,6 +68,72 @@ __device__ __forceinline__ void load_block_fwht(const float* __restrict__ src, i
   for (int vi = 0; vi < VEC; ++vi) fwht_regs<N>(v[vi]);
 }
 
+// Quantise the block a lane holds (v[vi][k]: column vi of the lane, transformed row k)
+// and drop the kept rows' codes into the LDS tile at byte `off` of the lane's rows.
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ void store_block_codes(const float (&v)[VEC][N], uint8_t* tile, int lane,
+                                                  int off, int TBP, const KeepMap& map, float inv,
+                                                  int rounding) {
+  constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+#pragma unroll
+  for (int vi = 0; vi < VEC; ++vi) {
+    uint8_t* dst = tile + (vi * 64 + lane) * TBP + off;
+    if constexpr (KIND == kKeepGeneric) {
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const int p = map.pos[k];
+        if (p >= 0) dst[p] = (uint8_t)quant_code(v[vi][k], inv, QMAX, rounding);
+      }
+    } else if constexpr (KIND == kKeepAll4) {
+#pragma unroll
+      for (int k8 = 0; k8 < N / 8; ++k8) {
+        uint32_t d = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          d |= (uint32_t)(quant_code(v[vi][k8 * 8 + e], inv, QMAX, rounding) & 0xF) << (4 * e);
+        reinterpret_cast<uint32_t*>(dst)[k8] = d;
+      }
+    } else {
+      constexpr int RK = KIND == kKeepLowHalf ? N / 2 : N;
+#pragma unroll
+      for (int j4 = 0; j4 < RK / 4; ++j4) {
+        uint32_t d = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = j4 * 4 + e;
+          const int k = KIND == kKeepLowHalf ? lowpass_row(N, j) : j;
+          d |= (uint32_t)(quant_code(v[vi][k], inv, QMAX, rounding) & 0xFF) << (8 * e);
+        }
+        reinterpret_cast<uint32_t*>(dst)[j4] = d;
+      }
+    }
+  }
+}
+
+// Write the LDS tile out as contiguous runs per column; the last row tile also
+// zero-fills up to the pitch.
+template <int VEC>
+__device__ __forceinline__ void write_out_tile(const uint8_t* tile, int TB, int TBP, int64_t tx,
+                                               int64_t ty, int64_t nblk, int kbw, int64_t C,
+                                               int64_t pitch, uint8_t* __restrict__ codes) {
+  constexpr int CT = 64 * VEC;
+  const int tid = threadIdx.x;
+  const int64_t tile_off = ty * TB;
+  int64_t cover = (ty == (nblk + 4 * kbw - 1) / (4 * kbw) - 1) ? pitch - tile_off : TB;
+  if (cover > pitch - tile_off) cover = pitch - tile_off;
+  const int cdw = (int)(cover >> 2), tdw = TB >> 2;
+  for (int idx = tid; idx < CT * cdw; idx += 256) {
+    const int col = idx / cdw, dw = idx - col * cdw;
+    const int64_t c = tx * CT + col;
+    if (c < C) {
+      const int row = (col % VEC) * 64 + col / VEC;
+      const uint32_t val = dw < tdw ? *reinterpret_cast<const uint32_t*>(tile + row * TBP + 4 * dw) : 0u;
+      *reinterpret_cast<uint32_t*>(codes + c * pitch + tile_off + 4 * dw) = val;
+    }
+  }
+}
+
 // Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
 // grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
 template <int N, int VEC, int KIND>
@@ -146,61 +212,240 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
     if (gb >= nblk || !col_ok) continue;
     float v[VEC][N];
     load_block_fwht<N, VEC>(x + gb * N * C + c0, C, v);
-#pragma unroll
-    for (int vi = 0; vi < VEC; ++vi) {
-      uint8_t* dst = tile + (vi * 64 + lane) * TBP + slot * bpb;
-      if constexpr (KIND == kKeepGeneric) {
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-          const int p = map.pos[k];
-          if (p >= 0) dst[p] = (uint8_t)quant_code(v[vi][k], inv, QMAX, rounding);
-        }
-      } else if constexpr (KIND == kKeepAll4) {
-#pragma unroll
-        for (int k8 = 0; k8 < N / 8; ++k8) {
-          uint32_t d = 0;
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            d |= (uint32_t)(quant_code(v[vi][k8 * 8 + e], inv, QMAX, rounding) & 0xF) << (4 * e);
-          reinterpret_cast<uint32_t*>(dst)[k8] = d;
-        }
-      } else {
-        constexpr int RK = KIND == kKeepLowHalf ? N / 2 : N;
-#pragma unroll
-        for (int j4 = 0; j4 < RK / 4; ++j4) {
-          uint32_t d = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int j = j4 * 4 + e;
-            const int k = KIND == kKeepLowHalf ? lowpass_row(N, j) : j;
-            d |= (uint32_t)(quant_code(v[vi][k], inv, QMAX, rounding) & 0xFF) << (8 * e);
-          }
-          reinterpret_cast<uint32_t*>(dst)[j4] = d;
-        }
-      }
-    }
+    store_block_codes<N, VEC, KIND>(v, tile, lane, slot * bpb, TBP, map, inv, rounding);
   }
   __syncthreads();
 
-  // Contiguous runs per column; the last row tile also zero-fills up to the pitch.
-  const int64_t tile_off = ty * TB;
-  int64_t cover = (ty == (nblk + 4 * kbw - 1) / (4 * kbw) - 1) ? pitch - tile_off : TB;
-  if (cover > pitch - tile_off) cover = pitch - tile_off;
-  const int cdw = (int)(cover >> 2), tdw = TB >> 2;
-  for (int idx = tid; idx < CT * cdw; idx += 256) {
-    const int col = idx / cdw, dw = idx - col * cdw;
-    const int64_t c = tx * CT + col;
-    if (c < C) {
-      const int row = (col % VEC) * 64 + col / VEC;
-      const uint32_t val = dw < tdw ? *reinterpret_cast<const uint32_t*>(tile + row * TBP + 4 * dw) : 0u;
-      *reinterpret_cast<uint32_t*>(codes + c * pitch + tile_off + 4 * dw) = val;
+  write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, kbw, C, pitch, codes);
+}
+
+// Largest kept |value| of a transformed block.
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ float kept_absmax(const float (&v)[VEC][N], const KeepMap& map) {
+  float m = 0.0f;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    bool kept;
+    if constexpr (KIND == kKeepGeneric) kept = map.pos[k] >= 0;
+    else if constexpr (KIND == kKeepLowHalf) kept = (k & 1) == 0;  // even natural rows
+    else kept = true;
+    if (kept) {
+#pragma unroll
+      for (int vi = 0; vi < VEC; ++vi) m = fmaxf(m, fabsf(v[vi][k]));
     }
   }
+  return m;
 }
+
+// Column transform restricted to the even natural rows (the N/2 lowest sequencies):
+// those outputs only take the sum branch of stage h = 1, so s[j] = v[2j] + v[2j+1]
+// followed by the N/2-point transform gives output row 2j' at s[j'] with the same
+// additions in the same order as the full transform.
+template <int N>
+__device__ __forceinline__ void fwht_even_rows(const float (&v)[N], float (&s)[N / 2]) {
+#pragma unroll
+  for (int j = 0; j < N / 2; ++j) s[j] = v[2 * j] + v[2 * j + 1];
+  fwht_regs<N / 2>(s);
+}
+
+// Values a lane keeps per column of a block: only the kept half when that is known at
+// compile time.
+template <int N, int KIND>
+constexpr int kept_vals() { return KIND == kKeepLowHalf ? N / 2 : N; }
+
+// Load one block and return its transformed values in kept form: all N natural rows, or
+// (kKeepLowHalf) the even natural rows, row 2j' at index j'.
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ void load_block_kept(const float* __restrict__ src, int64_t C,
+                                                float (&v)[VEC][kept_vals<N, KIND>()]) {
+  if constexpr (KIND == kKeepLowHalf) {
+    float full[VEC][N];
+    using VT = typename VecT<VEC>::type;
+    VT q[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) q[k] = *reinterpret_cast<const VT*>(src + (int64_t)k * C);
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      float o[VEC];
+      unpack_vec<VEC>(q[k], o);
+#pragma unroll
+      for (int vi = 0; vi < VEC; ++vi) full[vi][k] = o[vi];
+    }
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) fwht_even_rows<N>(full[vi], v[vi]);
+  } else {
+    load_block_fwht<N, VEC>(src, C, v);
+  }
+}
+
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ float kept_form_absmax(const float (&v)[VEC][kept_vals<N, KIND>()],
+                                                  const KeepMap& map) {
+  if constexpr (KIND == kKeepLowHalf) {
+    float m = 0.0f;
+#pragma unroll
+    for (int k = 0; k < N / 2; ++k) {
+#pragma unroll
+      for (int vi = 0; vi < VEC; ++vi) m = fmaxf(m, fabsf(v[vi][k]));
+    }
+    return m;
+  } else {
+    return kept_absmax<N, VEC, KIND>(v, map);
+  }
+}
+
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ void store_kept_form_codes(const float (&v)[VEC][kept_vals<N, KIND>()],
+                                                      uint8_t* tile, int lane, int off, int TBP,
+                                                      const KeepMap& map, float inv, int rounding) {
+  if constexpr (KIND == kKeepLowHalf) {
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) {
+      uint32_t* dst = reinterpret_cast<uint32_t*>(tile + (vi * 64 + lane) * TBP + off);
+#pragma unroll
+      for (int j4 = 0; j4 < N / 8; ++j4) {
+        uint32_t d = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int k = lowpass_row(N, j4 * 4 + e) >> 1;
+          d |= (uint32_t)(quant_code(v[vi][k], inv, 127, rounding) & 0xFF) << (8 * e);
+        }
+        dst[j4] = d;
+      }
+    }
+  } else {
+    store_block_codes<N, VEC, KIND>(v, tile, lane, off, TBP, map, inv, rounding);
+  }
+}
+
+// Maximum over the 256 threads of a workgroup, returned to all of them.
+__device__ __forceinline__ float workgroup_max(float m) {
+  __shared__ float s_wg[4];
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) s_wg[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_wg[0], s_wg[1]), fmaxf(s_wg[2], s_wg[3]));
+  __syncthreads();
+  return m;
+}
+
+// Single-pass variant for tensors that fit in the register files of the resident
+// workgroups: every workgroup keeps its transformed tile (4*KB blocks x 64*VEC columns)
+// in registers, publishes the tile's kept abs-max, collects everybody else's, and
+// quantises from registers: one read of the input, one launch.
+//
+// Exchange: slots[b] = (tag << 32 | float bits) written with one 64-bit device-scope
+// atomic store; a slot counts once it carries this launch's tag, so the memory needs no
+// initialisation and no fences.  Waiting is bounded: after `wait_ticks` of the 100 MHz
+// wall clock a workgroup computes the maxima still missing itself (each is a pure
+// function of that tile's input), so every wave finishes whether or not the other
+// workgroups are resident, and the result does not depend on who computed what.
+template <int N, int VEC, int KIND, int KB>
+__global__ __launch_bounds__(256) void col_quant_onepass_kernel(
+    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding,
+    unsigned long long* __restrict__ slots, uint32_t tag, long long wait_ticks,
+    uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scale) {
+  constexpr int CT = 64 * VEC;
+  constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  extern __shared__ __align__(16) uint8_t tile[];
+  __shared__ int s_nmiss;
+  __shared__ uint32_t s_miss[64];   // bit b of word b/32: slot b timed out (grid <= 2048)
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
+  const int TB = 4 * KB * bpb, TBP = TB + 4;
+  const int64_t nblk = R / N;
+  const int64_t tiles_x = (C + CT - 1) / CT;
+  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  const int64_t c0 = tx * CT + lane * VEC;
+  const bool col_ok = c0 < C;
+
+  float v[KB][VEC][kept_vals<N, KIND>()];
+  float m = 0.0f;
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    const int64_t gb = ty * 4 * KB + w * KB + kb;
+    if (gb < nblk && col_ok) {
+      load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v[kb]);
+      m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v[kb], map));
+    }
+  }
+  m = workgroup_max(m);
+  if (tid == 0)
+    __hip_atomic_store(&slots[blockIdx.x], ((unsigned long long)tag << 32) | __float_as_uint(m),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid < 64) s_miss[tid] = 0u;
+  if (tid == 0) s_nmiss = 0;
+  __syncthreads();
+
+  // collect the other workgroups' maxima, waiting a bounded time for each
+  const long long t0 = wall_clock64();
+  float amax = m;
+  for (int b = tid; b < (int)gridDim.x; b += 256) {
+    if (b == (int)blockIdx.x) continue;
+    bool got = false;
+    for (int polls = 0; polls < (1 << 16); ++polls) {   // second bound, should the clock stall
+      const unsigned long long sv =
+          __hip_atomic_load(&slots[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((uint32_t)(sv >> 32) == tag) {
+        amax = fmaxf(amax, __uint_as_float((uint32_t)sv));
+        got = true;
+        break;
+      }
+      if (wall_clock64() - t0 > wait_ticks) break;
+    }
+    if (!got) {
+      atomicOr(&s_miss[b >> 5], 1u << (b & 31));
+      atomicAdd(&s_nmiss, 1);
+    }
+  }
+  __syncthreads();
+  if (s_nmiss > 0) {   // workgroup-uniform
+    for (int b = 0; b < (int)gridDim.x; ++b) {
+      if (!((s_miss[b >> 5] >> (b & 31)) & 1u)) continue;
+      const int64_t btx = b % tiles_x, bty = b / tiles_x;
+      const int64_t bc0 = btx * CT + lane * VEC;
+      float mm = 0.0f;
+      for (int kb = 0; kb < KB; ++kb) {
+        const int64_t gb = bty * 4 * KB + w * KB + kb;
+        if (gb < nblk && bc0 < C) {
+          float t[VEC][kept_vals<N, KIND>()];
+          load_block_kept<N, VEC, KIND>(x + gb * N * C + bc0, C, t);
+          mm = fmaxf(mm, kept_form_absmax<N, VEC, KIND>(t, map));
+        }
+      }
+      amax = fmaxf(amax, mm);
+    }
+  }
+  amax = workgroup_max(amax);
+  const float inv = quant_inv(amax, QMAX);
+  if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
+
+  // slots of blocks past the end must read back as zero codes
+  if ((ty + 1) * 4 * KB > nblk) {
+    for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
+    __syncthreads();
+  }
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    const int slot = w * KB + kb;
+    const int64_t gb = ty * 4 * KB + slot;
+    if (gb < nblk && col_ok)
+      store_kept_form_codes<N, VEC, KIND>(v[kb], tile, lane, slot * bpb, TBP, map, inv, rounding);
+  }
+  __syncthreads();
+  write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, KB, C, pitch, codes);
+}
+
+// Columns per lane of the single-pass kernel: two for 16-row blocks, else one.
+__host__ __device__ constexpr int onepass_vec(int n) { return n == 16 ? 2 : 1; }
 
 // Host-side launch parameters shared by the two passes.
 struct ColPlan {
   int kind;
+  int kb_one;           // > 0: single-pass kernel with this many blocks per wave
+  int64_t tiles_one;
+  size_t lds_one;
   int vec_a, kbw_a;     // abs-max pass: wide loads, few registers beyond the block itself
   int absmax_grid;
   int vec_q, kbw_q;     // quantise pass: narrow tiles, more waves in flight

@@ -8,8 +8,9 @@ namespace hot {
 constexpr int kWave = 64;
 
 // ---- cross-lane exchange: value held by lane (id ^ MASK) -------------------
-// MASK 1, 2 use DPP quad permutes, 4..16 the ds_swizzle bit mode (no LDS memory
-// is touched), 32 swaps the wave halves.
+// MASK 1..8 are DPP permutes on the vector pipe (4 and 8 as two mirrors: reversing 4
+// then 8 lanes exchanges the halves of every 8, reversing 8 then 16 those of every 16);
+// 16 uses the ds_swizzle bit mode (no LDS memory is touched), 32 swaps the wave halves.
 template <int MASK>
 __device__ __forceinline__ float lane_xor(float v) {
   int x = __float_as_int(v);
@@ -18,7 +19,13 @@ __device__ __forceinline__ float lane_xor(float v) {
     r = __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
   } else if constexpr (MASK == 2) {
     r = __builtin_amdgcn_mov_dpp(x, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
-  } else if constexpr (MASK == 4 || MASK == 8 || MASK == 16) {
+  } else if constexpr (MASK == 4) {
+    const int t = __builtin_amdgcn_mov_dpp(x, 0x1B, 0xF, 0xF, true);   // quad_perm [3,2,1,0]
+    r = __builtin_amdgcn_mov_dpp(t, 0x141, 0xF, 0xF, true);            // row_half_mirror
+  } else if constexpr (MASK == 8) {
+    const int t = __builtin_amdgcn_mov_dpp(x, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    r = __builtin_amdgcn_mov_dpp(t, 0x140, 0xF, 0xF, true);            // row_mirror
+  } else if constexpr (MASK == 16) {
     r = __builtin_amdgcn_ds_swizzle(x, (MASK << 10) | 0x1F); // and 0x1F, or 0, xor MASK
   } else {
     static_assert(MASK == 32, "lane_xor mask");
@@ -39,10 +46,12 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // One butterfly stage across lanes: the lane whose MASK bit is clear holds the
 // lower element a, its partner the upper element b; (a, b) -> (a + b, a - b).
+// The upper lane adds its own value with the sign flipped: p + (-v) is p - v exactly.
 template <int MASK>
 __device__ __forceinline__ float butterfly_lanes(float v, bool upper) {
-  float p = lane_xor<MASK>(v);
-  return upper ? (p - v) : (v + p);
+  const float p = lane_xor<MASK>(v);
+  const float s = __int_as_float(__float_as_int(v) ^ (upper ? (int)0x80000000 : 0));
+  return p + s;
 }
 
 // In-register Walsh-Hadamard butterflies of a length-N array (Sec. 3.1), stages

@@ -57,8 +57,19 @@ struct GwLayout {
   GemmPlan plan;
   size_t scalars, qg, partial, total;
 };
+// hot_linear_backward: the g_x layout first (so its operand view applies unchanged),
+// then the per-token abs-max partials and the g_w operands.
+struct FusedLayout {
+  GxLayout gx;
+  GwLayout gw;                        // pitch / plan only; offsets below
+  size_t s_gh, rowpart, qgh, partial, total;
+};
 struct SelLayout {
   size_t scalars, rowmax, partial, total;
+};
+struct WeightLayout {
+  int64_t pitch;
+  size_t codes, total;
 };
 struct ActLayout {
   int64_t Lr, pitch;
@@ -68,13 +79,16 @@ struct ActLayout {
 GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I);
 GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I);
 SelLayout sel_layout(const Config& c, int64_t L, int64_t O);
+FusedLayout fused_layout(const Config& c, int64_t L, int64_t O, int64_t I);
 ActLayout act_layout(const Config& c, int64_t L, int64_t I);
+WeightLayout weight_layout(const Config& c, int64_t O, int64_t I);
 
 
 // Kernel roles for the optional stage timer (names in profile.hip).
 enum Stage {
   kStFill = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
-  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStGwReduce
+  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStGwReduce, kStGyFusedAbsmax,
+  kStGyFusedQuant
 };
 void stage_begin(int stage, hipStream_t s);
 void stage_end(int stage, hipStream_t s);
@@ -106,6 +120,20 @@ hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& 
                             const KeepMap& map, bool identity, int bits, uint8_t* codes,
                             int64_t pitch, float* scale, float* partials, hipStream_t s,
                             int stage_absmax, int stage_quant);
+
+// Both views of g_y [L x O] from shared reads (block sizes 16 and 32): token rows
+// rotated along O -> qg [L x pitch_g] with scales sg ([L] per token, [1] per tensor),
+// and the HLA view along L -> qgh [O x pitch_h] with scale s_gh.  part_hla / part_row:
+// kMaxPartials floats each; rowpart: gy_fused_tiles_x(O) * L floats (per token only).
+bool gy_fused_supported(const Config& c);
+int64_t gy_fused_tiles_x(int64_t O);
+hipError_t launch_gy_fused(const float* g_y, int64_t L, int64_t O, const Config& cfg, bool per_token,
+                           uint8_t* qg, int64_t pitch_g, float* sg, uint8_t* qgh, int64_t pitch_h,
+                           float* s_gh, float* part_hla, float* part_row, float* rowpart,
+                           hipStream_t s, int stage_absmax, int stage_quant);
+
+// Bounded wait of the single-pass column kernel (microseconds; < 0: always two passes).
+void set_exchange_wait_us(int us);
 
 // C[M x N] = A[M x K] . B[N x K]^T on K-contiguous code rows (pitch bytes each,
 // k_bytes = K * bits / 8 rounded up to the pitch alignment).

@@ -48,6 +48,12 @@ def test_act_buffer_is_one_eighth_of_fp32():
     assert hot.hot_act_buffer_bytes(hot.Config(block=24), 480, 768) == 0
 
 
+def test_weight_buffer_is_a_header_plus_padded_code_rows():
+    assert hot.hot_weight_buffer_bytes(hot.Config(), 768, 768) == 256 + 768 * 384
+    assert hot.hot_weight_buffer_bytes(hot.Config(gx_bits=8), 144, 10) == 256 + 10 * 256
+    assert hot.hot_weight_buffer_bytes(hot.Config(), 100, 10) == 0
+
+
 def test_workspace_covers_the_documented_operands():
     cfg = hot.Config()
     L, O, I = 512, 768, 768
@@ -89,6 +95,16 @@ def test_argument_shape_and_workspace_errors_precede_any_launch():
     assert lib.hot_compress_activation(c, fake, 40, 64, fake, fake, big, None) == hot.HOT_ERR_SHAPE
     assert lib.hot_compress_activation(c, fake, 64, 64, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
     assert lib.hot_compress_activation(c, None, 64, 64, fake, fake, big, None) == hot.HOT_ERR_ARG
+    assert lib.hot_linear_backward(c, fake, fake, None, 64, 64, 64, 1, fake, fake, fake, big, None) == hot.HOT_ERR_ARG
+    assert lib.hot_linear_backward(c, fake, fake, fake, 72, 64, 64, 1, fake, fake, fake, big, None) == hot.HOT_ERR_SHAPE
+    assert lib.hot_linear_backward(c, fake, fake, fake, 64, 72, 64, 1, fake, fake, fake, big, None) == hot.HOT_ERR_SHAPE
+    assert lib.hot_linear_backward(c, fake, fake, fake, 64, 64, 64, 1, fake, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
+    assert lib.hot_quantize_weight(c, fake, 72, 64, fake, fake, big, None) == hot.HOT_ERR_SHAPE
+    assert lib.hot_quantize_weight(c, fake, 64, 64, None, fake, big, None) == hot.HOT_ERR_ARG
+    assert lib.hot_quantize_weight(c, fake, 64, 64, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
+    assert lib.hot_linear_backward_gx_cached(c, fake, fake, 64, 72, 64, 1, fake, fake, big, None) == hot.HOT_ERR_SHAPE
+    assert lib.hot_linear_backward_gx_cached(c, fake, fake, 64, 64, 64, 1, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
+    assert lib.hot_linear_backward_gx_cached(c, fake, fake, 64, 64, 64, 3, fake, fake, big, None) == hot.HOT_ERR_ARG
     ch = C.c_int(0)
     assert lib.hot_select_quantizer(c, fake, 64, 64, None, None, None, fake, big, None) == hot.HOT_ERR_ARG
     assert lib.hot_select_quantizer(c, fake, 64, 70, C.byref(ch), None, None, fake, big, None) == hot.HOT_ERR_SHAPE

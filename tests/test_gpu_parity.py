@@ -268,6 +268,8 @@ def test_config2_full_size_in_bench_configuration():
     check_gx(hot, cfg, gy, w, True, "cfg2 per-token")
     check_gx(hot, cfg, gy, w, False, "cfg2 per-tensor")
     check_gw(hot, cfg, gy, x, "cfg2")
+    check_fused(hot, cfg, gy, x, w, True, "cfg2 one call, per-token")
+    check_fused(hot, cfg, gy, x, w, False, "cfg2 one call, per-tensor")
     L, I = x.shape
     # 12.5 % of fp32 plus the row padding to 128 bytes and the header
     assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((L // 2 + 127) // 128 * 128)
@@ -296,6 +298,7 @@ def test_workload_shaped_layers_on_a_token_subrange(name, L):
                  f"mse_token={m_tok:.3e} mse_tensor={m_ten:.3e}")
         check_gx(hot, cfg, gy, w, per_token, f"{name}.{layer.name}")
         check_gw(hot, cfg, gy, x, f"{name}.{layer.name}")
+        check_fused(hot, cfg, gy, x, w, per_token, f"{name}.{layer.name}")
 
 
 def test_large_token_count_sampled_rows():
@@ -333,3 +336,165 @@ def test_large_token_count_sampled_rows():
     assert np.array_equal(acc[rows], acc_rows)
     ref_rows = oracle.dequant(acc_rows, sg_ref[rows], sw_ref[0], cfg.block)
     assert_close_maxnorm(gx.cpu().numpy()[rows], ref_rows, "cfg3 proj g_x rows")
+
+
+# ---- one-call backward: both gradients from shared reads of g_y --------------------
+
+def check_fused(hot, cfg, gy, x, w, per_token, what):
+    """hot_linear_backward against the oracle's two paths, stage by stage."""
+    L, O = gy.shape
+    I = w.shape[1]
+    _say(f"[fused] {what} L={L} O={O} I={I} n={cfg.block} r={cfg.keep} keep={cfg.keep_idx} "
+         f"bits={cfg.gx_bits} token={per_token} round={cfg.rounding}")
+    keep = None if cfg.keep_idx is None else list(cfg.keep_idx)
+    ref_x = oracle.backward_gx(gy.numpy(), w.numpy(), cfg.block, bits=cfg.gx_bits, per_token=per_token,
+                               rounding=cfg.rounding)
+    codes_ref, sx_ref = oracle.compress_activation(x.numpy(), cfg.block, cfg.keep, keep=keep,
+                                                   rounding=cfg.rounding)
+    ref_w = oracle.backward_gw(gy.numpy(), codes_ref, sx_ref, cfg.block, cfg.keep, keep=keep,
+                               rounding=cfg.rounding)
+    assert ref_x["overflow"] == 0 and ref_w["overflow"] == 0
+    gyd, xd, wd = gy.cuda(), x.cuda(), w.cuda()
+    act = hot.alloc_act_buffer(cfg, L, I)
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    ws.fill_(0x5A)   # stale contents must not matter
+    hot.hot_compress_activation(cfg, xd, act, ws)
+    gx = torch.empty((L, I), dtype=torch.float32, device="cuda")
+    gw = torch.empty((O, I), dtype=torch.float32, device="cuda")
+    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
+    hot.hot_linear_backward(cfg, gyd, wd, act, q, gx, gw, ws)
+    if cfg.block != 64:
+        t = hot.hot_debug_fused_operands(cfg, ws, act, L, O, I, q)
+        torch.cuda.synchronize()
+        assert bits_equal(t["sg"].cpu().numpy(), ref_x["sg"]), f"{what}: g_y scales differ"
+        assert bits_equal(t["sw"].cpu().numpy(), ref_x["sw"]), f"{what}: w scale differs"
+        assert np.array_equal(t["qg"].cpu().numpy(), ref_x["qg"]), f"{what}: g_y codes differ"
+        assert np.array_equal(t["qw"].cpu().numpy(), ref_x["qw"]), f"{what}: w codes differ"
+        assert np.array_equal(t["acc_gx"].cpu().numpy().astype(np.int64), ref_x["acc"]), f"{what}: g_x accumulators differ"
+        assert bits_equal(t["sgh"].cpu().numpy(), [ref_w["sg"]]), f"{what}: HLA(g_y) scale differs"
+        assert np.array_equal(t["qgh"].cpu().numpy(), ref_w["qg"]), f"{what}: HLA(g_y) codes differ"
+        assert np.array_equal(t["acc_gw"].cpu().numpy().astype(np.int64), ref_w["acc"]), f"{what}: g_w accumulators differ"
+    torch.cuda.synchronize()
+    assert_close_maxnorm(gx.cpu().numpy(), ref_x["g_x"], what + " g_x")
+    assert_close_maxnorm(gw.cpu().numpy(), ref_w["g_w"], what + " g_w")
+    # and bit for bit what the two separate calls give
+    gx2, gw2 = torch.empty_like(gx), torch.empty_like(gw)
+    hot.hot_linear_backward_gx(cfg, gyd, wd, q, gx2, ws)
+    hot.hot_linear_backward_gw(cfg, gyd, act, I, gw2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gx, gx2) and torch.equal(gw, gw2), f"{what}: differs from the separate calls"
+
+
+FUSED_CASES = [
+    # L, O, I, n, r, keep_idx, bits
+    (16, 16, 4, 16, 8, None, 4),          # one block
+    (64, 48, 24, 16, 8, None, 4),         # a third of a column tile
+    (272, 144, 72, 16, 8, None, 4),       # ragged column tile, L' off the pitch
+    (512, 416, 136, 32, 16, None, 4),     # several column tiles, ragged last one
+    (2080, 320, 140, 32, 16, None, 4),    # ragged last row tile (65 blocks)
+    (512, 384, 136, 32, 16, None, 8),     # INT8 token codes
+    (240, 160, 72, 16, 3, None, 4),       # odd rank: generic kept-row list
+    (256, 128, 64, 16, 4, [5, 0, 9, 14], 8),
+    (256, 128, 64, 32, 32, None, 4),      # full rank in sequency order
+    (1024, 192, 260, 64, 32, None, 4),    # block size without shared passes
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES)
+@pytest.mark.parametrize("per_token", [True, False])
+def test_fused_backward_small_shapes(case, per_token):
+    L, O, I, n, r, keep_idx, bits = case
+    hot = _hot()
+    x, w, gy = make(L, O, I, seed=21, gy_kind="tok_outlier" if per_token else "chan_outlier")
+    cfg = hot.Config(block=n, keep=r, keep_idx=keep_idx, gx_bits=bits)
+    check_fused(hot, cfg, gy, x, w, per_token, "fused small")
+
+
+def test_fused_backward_nearest_rounding_and_zero_tokens():
+    hot = _hot()
+    x, w, gy = make(192, 256, 96, seed=22)
+    gy[17] = 0.0
+    gy[64:96] = 0.0     # a whole block of zero tokens
+    check_fused(hot, hot.Config(block=32, keep=16, rounding=0), gy, x, w, True, "fused rne zeros")
+    check_fused(hot, hot.Config(block=16, keep=8), torch.zeros(64, 64), x[:64], w[:64], False, "fused all zero")
+
+
+def test_fused_backward_config1_full():
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg1_single_512x768x768"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    check_fused(hot, hot.Config(block=wl.block, keep=wl.keep), gy, x, w, True, "fused cfg1")
+
+
+# ---- frozen weights: H.w quantised once, g_x only (Sec. 5.3) -------------------------
+
+@pytest.mark.parametrize("n,bits,per_token", [(16, 4, True), (32, 4, False), (64, 8, True)])
+def test_frozen_weight_gx_matches_oracle_and_uncached_call(n, bits, per_token):
+    hot = _hot()
+    L, O, I = 264, 448, 136
+    x, w, gy = make(L, O, I, seed=31)
+    cfg = hot.Config(block=n, keep=n // 2, gx_bits=bits)
+    _say(f"[gx cached] L={L} O={O} I={I} n={n} bits={bits} token={per_token}")
+    ref = oracle.backward_gx(gy.numpy(), w.numpy(), n, bits=bits, per_token=per_token, rounding=cfg.rounding)
+    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
+    wd = w.cuda()
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    wq = hot.alloc_weight_buffer(cfg, O, I)
+    hot.hot_quantize_weight(cfg, wd, wq, ws)
+    codes, sw = hot.hot_debug_unpack_weight(cfg, wq, O, I)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), ref["qw"]) and bits_equal(sw.cpu().numpy(), ref["sw"])
+    ws.fill_(0x33)   # nothing of the weight pass may be needed from ws afterwards
+    gx = torch.empty((L, I), device="cuda")
+    for step in range(2):   # second step: another g_y against the same cached weights
+        g = gy if step == 0 else hot_inputs.make_gy("t4", L, O, 32, "step2")
+        r = ref if step == 0 else oracle.backward_gx(g.numpy(), w.numpy(), n, bits=bits, per_token=per_token,
+                                                     rounding=cfg.rounding)
+        hot.hot_linear_backward_gx_cached(cfg, g.cuda(), wq, I, q, gx, ws)
+        taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q, want_acc=False)
+        torch.cuda.synchronize()
+        assert np.array_equal(taps["qg"].cpu().numpy(), r["qg"]) and bits_equal(taps["sg"].cpu().numpy(), r["sg"])
+        assert_close_maxnorm(gx.cpu().numpy(), r["g_x"], f"cached g_x step {step}")
+        gx2 = torch.empty_like(gx)
+        ws2 = hot.alloc_workspace(cfg, L, O, I)
+        hot.hot_linear_backward_gx(cfg, g.cuda(), wd, q, gx2, ws2)
+        torch.cuda.synchronize()
+        assert torch.equal(gx, gx2)
+
+
+# ---- column quantiser: single-pass and two-pass kernels must agree with the oracle ----
+
+@pytest.fixture
+def exchange_wait():
+    hot = _hot()
+    yield hot.hot_debug_set_exchange_wait_us
+    hot.hot_debug_set_exchange_wait_us(200)
+
+
+@pytest.mark.parametrize("wait_us", [-1, 0, 200])
+def test_column_quantiser_paths(exchange_wait, wait_us):
+    """wait < 0: two-pass kernels; 0: single pass where every workgroup computes the other
+    workgroups' maxima itself (what happens when they are late); 200: the default."""
+    hot = _hot()
+    exchange_wait(wait_us)
+    for (L, O, I, n, r, keep_idx) in [(272, 130, 72, 16, 8, None), (2048, 300, 140, 16, 8, None),
+                                      (1024, 224, 260, 32, 16, None), (1024, 96, 260, 64, 32, None),
+                                      (240, 64, 72, 16, 3, None), (256, 64, 64, 16, 4, [5, 0, 9, 14])]:
+        x, w, gy = make(L, O, I, seed=41)
+        cfg = hot.Config(block=n, keep=r, keep_idx=keep_idx)
+        check_gw(hot, cfg, gy, x, f"wait={wait_us}")
+        if O % n == 0:
+            check_gx(hot, cfg, gy, w, True, f"wait={wait_us}")
+            check_gx(hot, hot.Config(block=n, keep=r, keep_idx=keep_idx, gx_bits=8), gy, w, False, f"wait={wait_us}")
+
+
+def test_config2_two_pass_column_kernels(exchange_wait):
+    """configs[1] with the single-pass kernels switched off (x and w then take the same
+    two-pass kernels as tensors too large for the register files)."""
+    hot = _hot()
+    exchange_wait(-1)
+    wl = hot_inputs.WORKLOADS["cfg2_vitb_fc1"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    check_gx(hot, cfg, gy, w, True, "cfg2 two-pass")
+    check_gw(hot, cfg, gy, x, "cfg2 two-pass")
