@@ -45,6 +45,22 @@ def stage_model(L, O, I, n, r, gx_bits, per_token):
     return m
 
 
+def profiled_traffic(workload, role):
+    """HBM bytes per launch (fetched + written) of a kernel role, from the committed
+    rocprofv3 counter summary of this workload (FETCH_SIZE / WRITE_SIZE, scaled by a copy
+    of known size); None when no summary covers it."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                f = line.split()
+                if len(f) == 4 and f[0] == "traffic_bytes" and f[1] == role:
+                    return int(f[2]) + int(f[3])
+    except OSError:
+        pass
+    return None
+
+
 def probe_peaks(torch, hot):
     """Plain HBM read / write rate and raw int8 matrix rate of this machine (context only)."""
     out = {}
@@ -179,6 +195,8 @@ def main() -> int:
                     frac=round(d["TOPS"] / INT8_PEAK_TOPS, 4), traffic=None,
                     algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
 
+    if quant == "token" and not args.one_call:   # the configuration the counter runs measured
+        roof["traffic"] = profiled_traffic(wl.name, dominant)
     Lr = L // n * r
     ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
     value = ops_step / (ms_per_step * 1e-3) / 1e12
