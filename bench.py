@@ -61,6 +61,74 @@ def profiled_traffic(workload, role):
     return None
 
 
+def run_sweep(torch, hot, hot_inputs, wl, quantizer_flag):
+    """Forward-time compression of every layer of a workload, then the backward of every
+    layer (a chain when the workload says so: each g_x is the next lower layer's g_y).
+    Returns per-layer times (HIP events on the launch stream), buffer bytes and peak memory."""
+    n, r = wl.block, wl.keep
+    cfg = hot.Config(block=n, keep=r)
+    depth = int(wl.extra.get("depth", 0))
+    chain = depth > 0
+    layers = [(f"{d}.{l.name}", l) for d in range(depth) for l in wl.layers] if chain \
+        else [(l.name, l) for l in wl.layers]
+    torch.cuda.reset_peak_memory_stats()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    acts, rows = [], []
+    ws = torch.empty(max(hot.hot_workspace_bytes(cfg, l.L, l.O, l.I) for _, l in layers),
+                     dtype=torch.uint8, device="cuda")
+    fp32_bytes = act_bytes = 0
+    for name, l in layers:           # "forward": only what the backward will need is kept
+        x = hot_inputs.make_x(wl.x_kind, l.L, l.I, 0, f"{wl.name}.{name}", "cuda")
+        act = hot.alloc_act_buffer(cfg, l.L, l.I)
+        e0, e1 = ev(), ev()
+        e0.record()
+        hot.hot_compress_activation(cfg, x, act, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        rows.append(dict(layer=name, L=l.L, O=l.O, I=l.I, compress_us=round(e0.elapsed_time(e1) * 1e3, 1)))
+        acts.append(act)
+        fp32_bytes += 4 * l.L * l.I
+        act_bytes += act.numel()
+        del x
+    g_y = None
+    for k in range(len(layers) - 1, -1, -1):
+        name, l = layers[k]
+        w = hot_inputs.make_w(l.O, l.I, 0, f"{wl.name}.{name}", "cuda")
+        if g_y is None or not chain:
+            g_y = hot_inputs.make_gy(wl.gy_kind, l.L, l.O, 0, f"{wl.name}.{name}", "cuda")
+        quant = quantizer_flag or wl.quantizer
+        row = rows[k]
+        if quant == "select":
+            choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, g_y, ws)
+            quant = "token" if choice == hot.HOT_Q_PER_TOKEN else "tensor"
+            row.update(mse_token=m_tok, mse_tensor=m_ten)
+        q = hot.HOT_Q_PER_TOKEN if quant == "token" else hot.HOT_Q_PER_TENSOR
+        g_x = torch.empty((l.L, l.I), device="cuda")
+        g_w = torch.empty((l.O, l.I), device="cuda")
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        hot.hot_linear_backward_gx(cfg, g_y, w, q, g_x, ws)
+        e1.record()
+        hot.hot_linear_backward_gw(cfg, g_y, acts[k], l.I, g_w, ws)
+        e2.record()
+        torch.cuda.synchronize()
+        gx_us, gw_us = e0.elapsed_time(e1) * 1e3, e1.elapsed_time(e2) * 1e3
+        Lr = l.L // n * r
+        row.update(gy_quantizer=quant, gx_us=round(gx_us, 1), gw_us=round(gw_us, 1),
+                   gx_TOPS=round(2.0 * l.L * l.O * l.I / gx_us / 1e6, 1),
+                   gw_TOPS=round(2.0 * l.O * l.I * Lr / gw_us / 1e6, 1),
+                   finite=bool(torch.isfinite(g_x).all().item() and torch.isfinite(g_w).all().item()))
+        acts[k] = None
+        g_y = g_x if chain else None
+        del w, g_w
+    total_us = sum(x["compress_us"] + x["gx_us"] + x["gw_us"] for x in rows)
+    ops = sum(2.0 * l.L * l.O * l.I + 2.0 * l.O * l.I * (l.L // n * r) for _, l in layers)
+    return dict(workload=wl.name, layers=rows, total_us=round(total_us, 1),
+                effective_TOPS=round(ops / total_us / 1e6, 1),
+                act_buffer_bytes=act_bytes, act_fp32_bytes=fp32_bytes,
+                peak_device_bytes=int(torch.cuda.max_memory_allocated()))
+
+
 def probe_peaks(torch, hot):
     """Plain HBM read / write rate and raw int8 matrix rate of this machine (context only)."""
     out = {}
@@ -109,6 +177,10 @@ def main() -> int:
     ap.add_argument("--probe-peaks", action="store_true",
                     help="instead of the workload, time plain HBM read/write and a register-only "
                          "int8 matrix loop, and print them as JSON")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the timed step, run every layer of the workload once (compress "
+                         "all, then backward all; chained where the workload is a chain) and print "
+                         "per-layer times, buffer bytes and peak device memory as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of g_y (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -127,6 +199,10 @@ def main() -> int:
         print(json.dumps(probe_peaks(torch, hot)))
         return 0
     wl = hot_inputs.WORKLOADS[args.workload]
+    if args.sweep:
+        run_sweep(torch, hot, hot_inputs, wl, args.quantizer)   # warm-up: code objects, allocator
+        print(json.dumps(run_sweep(torch, hot, hot_inputs, wl, args.quantizer)))
+        return 0
     layer = wl.layers[0]
     L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep
     quant = args.quantizer or ("token" if wl.quantizer in ("token", "select") else "tensor")
