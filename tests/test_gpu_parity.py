@@ -301,41 +301,114 @@ def test_workload_shaped_layers_on_a_token_subrange(name, L):
         check_fused(hot, cfg, gy, x, w, per_token, f"{name}.{layer.name}")
 
 
-def test_large_token_count_sampled_rows():
-    """configs[2] proj at its full 50432 tokens: every code and scale is compared with the
-    oracle; the integer product is checked exactly on sampled token rows (oracle GEMM on
-    those rows) and on all rows through an exact int64 Freivalds identity C v = A (B v)."""
-    hot = _hot()
-    wl = hot_inputs.WORKLOADS["cfg3_vitb_block_b256"]
-    layer = wl.layers[1]
+def _amax_of(A):
+    return 127.0 if A.dtype == np.int8 else float(2 ** 31)
+
+
+def _matvec_exact(A, v, chunk=16384):
+    """A @ v for integer A (int8 codes or int32 accumulators) and integer v, exactly, in row
+    chunks (no full-size wide copy of A): float64 BLAS when every sum stays below 2^53,
+    else int64."""
+    v = np.asarray(v)
+    if float(np.abs(v.astype(np.float64)).sum()) * _amax_of(A) < 2.0 ** 53:
+        vf = v.astype(np.float64)
+        out = np.concatenate([A[i:i + chunk].astype(np.float64) @ vf for i in range(0, A.shape[0], chunk)])
+        return np.rint(out).astype(np.int64)
+    vi = v.astype(np.int64)
+    return np.concatenate([A[i:i + chunk].astype(np.int64) @ vi for i in range(0, A.shape[0], chunk)])
+
+
+def _vecmat_exact(u, A, chunk=16384):
+    """u @ A, same rules, accumulated over row chunks of A."""
+    u = np.asarray(u)
+    if float(np.abs(u.astype(np.float64)).sum()) * _amax_of(A) < 2.0 ** 53:
+        uf = u.astype(np.float64)
+        out = np.zeros(A.shape[1], dtype=np.float64)
+        for i in range(0, A.shape[0], chunk):
+            out += uf[i:i + chunk] @ A[i:i + chunk].astype(np.float64)
+        return np.rint(out).astype(np.int64)
+    ui = u.astype(np.int64)
+    out = np.zeros(A.shape[1], dtype=np.int64)
+    for i in range(0, A.shape[0], chunk):
+        out += ui[i:i + chunk] @ A[i:i + chunk].astype(np.int64)
+    return out
+
+
+def check_full_size_sampled(hot, wl, layer, what, per_token=True):
+    """One layer at its full size: every code and scale of every operand is compared with the
+    oracle; both integer products are checked on all outputs through exact Freivalds identities
+    C v = A (B v) and on sampled output rows against the oracle's GEMM, whose dequantised rows
+    bound the fp32 outputs."""
     L, O, I = layer.L, layer.O, layer.I
-    x, w, gy = hot_inputs.make_layer(wl, layer, seed=0)
-    cfg = hot.Config(block=wl.block, keep=wl.keep)
-    _say(f"[gx] cfg3 proj full L={L} O={O} I={I}")
-    T = oracle.transform_rows(gy.numpy(), cfg.block)
-    qg_ref, sg_ref = oracle.quantize(T, 4, True, oracle.PSEUDO_STOCHASTIC)
-    U = oracle.hla(w.numpy(), cfg.block, cfg.block, np.arange(cfg.block))
-    qw_ref, sw_ref = oracle.quantize(U, 4, False, oracle.PSEUDO_STOCHASTIC)
-    ws = hot.alloc_workspace(cfg, L, O, I)
-    gx = torch.empty((L, I), device="cuda")
-    hot.hot_linear_backward_gx(cfg, gy.cuda(), w.cuda(), hot.HOT_Q_PER_TOKEN, gx, ws)
-    taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, hot.HOT_Q_PER_TOKEN)
-    torch.cuda.synchronize()
-    assert np.array_equal(taps["qg"].cpu().numpy(), qg_ref)
-    assert bits_equal(taps["sg"].cpu().numpy(), sg_ref)
-    assert np.array_equal(taps["qw"].cpu().numpy(), qw_ref)
-    assert bits_equal(taps["sw"].cpu().numpy(), sw_ref)
-    acc = taps["acc"].cpu().numpy().astype(np.int64)
+    n, r = wl.block, wl.keep
+    cfg = hot.Config(block=n, keep=r)
+    xd, wd, gyd = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
+    x, w, gy = xd.cpu().numpy(), wd.cpu().numpy(), gyd.cpu().numpy()
     rng = np.random.default_rng(5)
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
+
+    _say(f"[gx] {what} full L={L} O={O} I={I} n={n}")
+    qg_ref, sg_ref = oracle.quantize(oracle.transform_rows(gy, n), 4, per_token, oracle.PSEUDO_STOCHASTIC)
+    qw_ref, sw_ref = oracle.quantize(oracle.hla(w, n, n, np.arange(n)), 4, False, oracle.PSEUDO_STOCHASTIC)
+    gx = torch.empty((L, I), device="cuda")
+    hot.hot_linear_backward_gx(cfg, gyd, wd, q, gx, ws)
+    taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q)
+    torch.cuda.synchronize()
+    assert np.array_equal(taps["qg"].cpu().numpy(), qg_ref), f"{what}: g_y codes differ"
+    assert bits_equal(taps["sg"].cpu().numpy(), sg_ref), f"{what}: g_y scales differ"
+    assert np.array_equal(taps["qw"].cpu().numpy(), qw_ref), f"{what}: w codes differ"
+    assert bits_equal(taps["sw"].cpu().numpy(), sw_ref), f"{what}: w scale differs"
+    acc = taps["acc"].cpu().numpy()
+    del taps
     v = rng.integers(-2048, 2048, size=I)
-    assert np.array_equal(acc @ v, qg_ref.astype(np.int64) @ (qw_ref.astype(np.int64) @ v))
+    assert np.array_equal(_matvec_exact(acc, v), _matvec_exact(qg_ref, _matvec_exact(qw_ref, v)))
     u = rng.integers(-2048, 2048, size=L)
-    assert np.array_equal(u @ acc, (u @ qg_ref.astype(np.int64)) @ qw_ref.astype(np.int64))
+    assert np.array_equal(_vecmat_exact(u, acc), _vecmat_exact(_vecmat_exact(u, qg_ref), qw_ref))
     rows = np.unique(np.concatenate([np.arange(0, 256), rng.integers(0, L, 512), np.arange(L - 200, L)]))
-    acc_rows, _ = oracle.igemm_nn(qg_ref[rows], qw_ref)
-    assert np.array_equal(acc[rows], acc_rows)
-    ref_rows = oracle.dequant(acc_rows, sg_ref[rows], sw_ref[0], cfg.block)
-    assert_close_maxnorm(gx.cpu().numpy()[rows], ref_rows, "cfg3 proj g_x rows")
+    acc_rows, bad = oracle.igemm_nn(qg_ref[rows], qw_ref)
+    assert bad == 0 and np.array_equal(acc[rows].astype(np.int64), acc_rows)
+    ref_rows = oracle.dequant(acc_rows, sg_ref[rows] if per_token else sg_ref, sw_ref[0], n)
+    assert_close_maxnorm(gx[torch.from_numpy(rows).cuda()].cpu().numpy(), ref_rows, what + " g_x rows")
+    del acc, qg_ref, gx
+
+    _say(f"[gw] {what} full L={L} O={O} I={I} n={n} r={r}")
+    keep = oracle.lowpass_index(n, r)
+    xc_ref, sx_ref = oracle.compress_activation(x, n, r)
+    gh_ref, sh_ref = oracle.quantize(oracle.hla(gy, n, r, keep), 8, False, oracle.PSEUDO_STOCHASTIC)
+    act = hot.alloc_act_buffer(cfg, L, I)
+    hot.hot_compress_activation(cfg, xd, act, ws)
+    codes, sx = hot.hot_debug_unpack_activation(cfg, act, L, I)
+    gw = torch.empty((O, I), device="cuda")
+    hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
+    taps = hot.hot_debug_gw_operands(cfg, ws, act, L, O, I)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), [sx_ref]) and np.array_equal(codes.cpu().numpy(), xc_ref), \
+        f"{what}: compressed activation differs"
+    assert bits_equal(taps["sg"].cpu().numpy(), sh_ref), f"{what}: HLA(g_y) scale differs"
+    assert np.array_equal(taps["qg"].cpu().numpy(), gh_ref), f"{what}: HLA(g_y) codes differ"
+    acc = taps["acc"].cpu().numpy()
+    v = rng.integers(-2048, 2048, size=I)
+    assert np.array_equal(_matvec_exact(acc, v), _vecmat_exact(_matvec_exact(xc_ref, v), gh_ref))
+    u = rng.integers(-2048, 2048, size=O)
+    assert np.array_equal(_vecmat_exact(u, acc), _vecmat_exact(_matvec_exact(gh_ref, u), xc_ref))
+    orow = np.unique(np.concatenate([np.arange(0, 64), rng.integers(0, O, 64), np.arange(O - 40, O)]))
+    acc_rows, bad = oracle.igemm_tn(np.ascontiguousarray(gh_ref[:, orow]), xc_ref)
+    assert bad == 0 and np.array_equal(acc[orow].astype(np.int64), acc_rows)
+    ref_rows = oracle.dequant(acc_rows, sh_ref, sx_ref, n)
+    assert_close_maxnorm(gw.cpu().numpy()[orow], ref_rows, what + " g_w rows")
+
+
+@pytest.mark.parametrize("name,idx", [("cfg3_vitb_block_b256", 0), ("cfg3_vitb_block_b256", 1),
+                                      ("cfg3_vitb_block_b256", 2), ("cfg3_vitb_block_b256", 3),
+                                      ("cfg4_llm7b_mlp", 0), ("cfg4_llm7b_mlp", 1),
+                                      ("cfg5_vitl_chain", 0), ("cfg5_vitl_chain", 1)])
+def test_full_size_layers_sampled(name, idx):
+    """Every layer of configs[2], [3] and [4] at its full token count (config 4: the 256x256
+    GEMM tiles and 64-row blocks; config 5: tensors beyond 2^31 bytes on either side)."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS[name]
+    check_full_size_sampled(hot, wl, wl.layers[idx], f"{name}.{wl.layers[idx].name}")
 
 
 # ---- one-call backward: both gradients from shared reads of g_y --------------------
