@@ -42,9 +42,9 @@ ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_defa
   const int64_t ta = tiles(p.vec_a, p.kbw_a);
   p.absmax_grid = (int)(ta < kMaxPartials ? ta : kMaxPartials);
   // Quantise pass: measured fastest with one column per lane (few registers, many
-  // waves) and enough blocks per wave for 128-byte output runs per column.
+  // waves) and enough blocks per wave for 256-byte output runs per column.
   p.vec_q = 1;
-  p.kbw_q = 32 / bpb;
+  p.kbw_q = 64 / bpb;
   p.kbw_q = p.kbw_q < 1 ? 1 : (p.kbw_q > 8 ? 8 : p.kbw_q);
   while (tiles(p.vec_q, p.kbw_q) < 512 && p.kbw_q > 1) p.kbw_q /= 2;
   p.tiles_q = tiles(p.vec_q, p.kbw_q);

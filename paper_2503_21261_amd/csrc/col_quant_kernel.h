@@ -134,91 +134,6 @@ __device__ __forceinline__ void write_out_tile(const uint8_t* tile, int TB, int 
   }
 }
 
-// Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
-// grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
-template <int N, int VEC, int KIND>
-__global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, int64_t R,
-                                                         int64_t C, KeepMap map, int kbw,
-                                                         float* __restrict__ partials) {
-  constexpr int CT = 64 * VEC;
-  __shared__ float s_max[4];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  const int64_t nblk = R / N;
-  const int64_t tiles_x = (C + CT - 1) / CT;
-  const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
-  float m = 0.0f;
-  for (int64_t t = blockIdx.x; t < tiles_x * tiles_y; t += gridDim.x) {
-    const int64_t tx = t % tiles_x, ty = t / tiles_x;
-    const int64_t c0 = tx * CT + lane * VEC;
-    if (c0 >= C) continue;
-    for (int kb = 0; kb < kbw; ++kb) {
-      const int64_t gb = ty * 4 * kbw + w * kbw + kb;
-      if (gb >= nblk) break;
-      float v[VEC][N];
-      load_block_fwht<N, VEC>(x + gb * N * C + c0, C, v);
-#pragma unroll
-      for (int k = 0; k < N; ++k) {
-        bool kept;
-        if constexpr (KIND == kKeepGeneric) kept = map.pos[k] >= 0;
-        else if constexpr (KIND == kKeepLowHalf) kept = (k & 1) == 0;  // even natural rows
-        else kept = true;
-        if (kept) {
-#pragma unroll
-          for (int vi = 0; vi < VEC; ++vi) m = fmaxf(m, fabsf(v[vi][k]));
-        }
-      }
-    }
-  }
-  m = wave_max(m);
-  if (lane == 0) s_max[w] = m;
-  __syncthreads();
-  if (tid == 0) partials[blockIdx.x] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-}
-
-// Quantise pass: one tile per workgroup.  LDS tile: row (vi*64 + lane) holds the code
-// bytes of column lane*VEC + vi (odd dword pitch: conflict-free for both the strided
-// writes and the row-wise read-out).
-template <int N, int VEC, int KIND>
-__global__ __launch_bounds__(256) void col_quant_kernel(
-    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding, int kbw,
-    const float* __restrict__ partials, int npartials, uint8_t* __restrict__ codes, int64_t pitch,
-    float* __restrict__ scale) {
-  constexpr int CT = 64 * VEC;
-  constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
-  constexpr int QMAX = (1 << (BITS - 1)) - 1;
-  extern __shared__ __align__(16) uint8_t tile[];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
-  const int TB = 4 * kbw * bpb;      // code bytes per column in this tile
-  const int TBP = TB + 4;            // odd number of dwords
-  const int64_t nblk = R / N;
-  const int64_t tiles_x = (C + CT - 1) / CT;
-  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
-  const int64_t c0 = tx * CT + lane * VEC;
-  const bool col_ok = c0 < C;
-
-  const float amax = block_max_of(partials, npartials);
-  const float inv = quant_inv(amax, QMAX);
-  if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
-  // slots of blocks past the end must read back as zero codes
-  if ((ty + 1) * 4 * kbw > nblk) {
-    for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
-    __syncthreads();
-  }
-
-  for (int kb = 0; kb < kbw; ++kb) {
-    const int slot = w * kbw + kb;
-    const int64_t gb = ty * 4 * kbw + slot;
-    if (gb >= nblk || !col_ok) continue;
-    float v[VEC][N];
-    load_block_fwht<N, VEC>(x + gb * N * C + c0, C, v);
-    store_block_codes<N, VEC, KIND>(v, tile, lane, slot * bpb, TBP, map, inv, rounding);
-  }
-  __syncthreads();
-
-  write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, kbw, C, pitch, codes);
-}
-
 // Largest kept |value| of a transformed block.
 template <int N, int VEC, int KIND>
 __device__ __forceinline__ float kept_absmax(const float (&v)[VEC][N], const KeepMap& map) {
@@ -327,6 +242,81 @@ __device__ __forceinline__ float workgroup_max(float m) {
   m = fmaxf(fmaxf(s_wg[0], s_wg[1]), fmaxf(s_wg[2], s_wg[3]));
   __syncthreads();
   return m;
+}
+
+// Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
+// grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
+template <int N, int VEC, int KIND>
+__global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, int64_t R,
+                                                         int64_t C, KeepMap map, int kbw,
+                                                         float* __restrict__ partials) {
+  constexpr int CT = 64 * VEC;
+  __shared__ float s_max[4];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t nblk = R / N;
+  const int64_t tiles_x = (C + CT - 1) / CT;
+  const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
+  float m = 0.0f;
+  for (int64_t t = blockIdx.x; t < tiles_x * tiles_y; t += gridDim.x) {
+    const int64_t tx = t % tiles_x, ty = t / tiles_x;
+    const int64_t c0 = tx * CT + lane * VEC;
+    if (c0 >= C) continue;
+    for (int kb = 0; kb < kbw; ++kb) {
+      const int64_t gb = ty * 4 * kbw + w * kbw + kb;
+      if (gb >= nblk) break;
+      float v[VEC][kept_vals<N, KIND>()];
+      load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v);
+      m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v, map));
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) s_max[w] = m;
+  __syncthreads();
+  if (tid == 0) partials[blockIdx.x] = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+}
+
+// Quantise pass: one tile per workgroup.  LDS tile: row (vi*64 + lane) holds the code
+// bytes of column lane*VEC + vi (odd dword pitch: conflict-free for both the strided
+// writes and the row-wise read-out).
+template <int N, int VEC, int KIND>
+__global__ __launch_bounds__(256) void col_quant_kernel(
+    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding, int kbw,
+    const float* __restrict__ partials, int npartials, uint8_t* __restrict__ codes, int64_t pitch,
+    float* __restrict__ scale) {
+  constexpr int CT = 64 * VEC;
+  constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  extern __shared__ __align__(16) uint8_t tile[];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
+  const int TB = 4 * kbw * bpb;      // code bytes per column in this tile
+  const int TBP = TB + 4;            // odd number of dwords
+  const int64_t nblk = R / N;
+  const int64_t tiles_x = (C + CT - 1) / CT;
+  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  const int64_t c0 = tx * CT + lane * VEC;
+  const bool col_ok = c0 < C;
+
+  const float amax = block_max_of(partials, npartials);
+  const float inv = quant_inv(amax, QMAX);
+  if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
+  // slots of blocks past the end must read back as zero codes
+  if ((ty + 1) * 4 * kbw > nblk) {
+    for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
+    __syncthreads();
+  }
+
+  for (int kb = 0; kb < kbw; ++kb) {
+    const int slot = w * kbw + kb;
+    const int64_t gb = ty * 4 * kbw + slot;
+    if (gb >= nblk || !col_ok) continue;
+    float v[VEC][kept_vals<N, KIND>()];
+    load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v);
+    store_kept_form_codes<N, VEC, KIND>(v, tile, lane, slot * bpb, TBP, map, inv, rounding);
+  }
+  __syncthreads();
+
+  write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, kbw, C, pitch, codes);
 }
 
 // Single-pass variant for tensors that fit in the register files of the resident
