@@ -571,3 +571,50 @@ def test_config2_two_pass_column_kernels(exchange_wait):
     cfg = hot.Config(block=wl.block, keep=wl.keep)
     check_gx(hot, cfg, gy, w, True, "cfg2 two-pass")
     check_gw(hot, cfg, gy, x, "cfg2 two-pass")
+
+
+# ---- maximum reduction lengths: accumulators at the edge of int32 ------------------------
+
+def _hadamard_np(n):
+    H = np.array([[1.0]])
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def test_gx_longest_reduction_with_saturated_codes():
+    """O at the documented limit with every code of both operands equal to +7 (inputs are
+    H t / n per block, so the rotated values are the constant t exactly): the INT4 operands
+    are fed to the matrix cores as 16 x code, so the internal sum 256 * 49 * O must still
+    fit int32, and the true accumulator is 49 * O everywhere."""
+    hot = _hot()
+    n, O, L, I = 64, 171136, 3, 5
+    assert O % n == 0 and 256 * 49 * O < 2 ** 31 <= 256 * 49 * (O + n)
+    H = _hadamard_np(n)
+    blk_g = (H @ np.full(n, 0.5)) / n           # exact: small dyadic values
+    blk_w = (H @ np.full(n, 0.25)) / n
+    gy = torch.from_numpy(np.tile(blk_g, (L, O // n)).astype(np.float32))
+    w = torch.from_numpy(np.tile(blk_w.reshape(n, 1), (O // n, I)).astype(np.float32))
+    cfg = hot.Config(block=n, keep=n // 2)
+    for per_token in (True, False):
+        ref, gx = check_gx(hot, cfg, gy, w, per_token, "longest O")
+        assert (ref["qg"] == 7).all() and (ref["qw"] == 7).all() and (ref["acc"] == 49 * O).all()
+
+
+def test_gw_longest_reduction_with_saturated_codes():
+    """L' at the documented limit with every INT8 code of both operands equal to +127:
+    127^2 * L' is the largest accumulator the g_w path can produce."""
+    hot = _hot()
+    n, r, O, I = 16, 8, 16, 16
+    Lr = 133120
+    L = Lr * n // r
+    assert 127 * 127 * Lr < 2 ** 31 and Lr <= 133144 < Lr + 128
+    H = _hadamard_np(n)
+    t = np.zeros(n)
+    t[oracle.lowpass_index(n, r)] = 2.0          # kept rows carry the constant, dropped rows 0
+    blk = (H @ t) / n
+    gy = torch.from_numpy(np.tile(blk.reshape(n, 1), (L // n, O)).astype(np.float32))
+    x = torch.from_numpy(np.tile((blk * 3.0).reshape(n, 1), (L // n, I)).astype(np.float32))
+    cfg = hot.Config(block=n, keep=r)
+    ref, gw = check_gw(hot, cfg, gy, x, "longest L'")
+    assert (ref["qg"] == 127).all() and (ref["acc"] == 127 * 127 * Lr).all()
