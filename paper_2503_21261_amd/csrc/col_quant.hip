@@ -49,25 +49,6 @@ ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_defa
   while (tiles(p.vec_q, p.kbw_q) < 512 && p.kbw_q > 1) p.kbw_q /= 2;
   p.tiles_q = tiles(p.vec_q, p.kbw_q);
   p.lds_q = (size_t)(64 * p.vec_q) * (4 * p.kbw_q * bpb + 4);
-  // Single pass: the smallest number of blocks per wave (most workgroups, most loads in
-  // flight) whose grid stays within what is resident at once; the launcher checks the
-  // kernel's real occupancy.  One column per lane (two for n = 16), at most 96 block
-  // values per lane.
-  p.kb_one = 0;
-  p.tiles_one = 0;
-  p.lds_one = 0;
-  const int vec1 = onepass_vec(n);
-  if (C % vec1 == 0) {
-    for (int kb = 1; kb <= 3 && kb * vec1 * n <= 96; ++kb) {
-      const int64_t t = tiles(vec1, kb);
-      if (t <= 512) {
-        p.kb_one = kb;
-        p.tiles_one = t;
-        p.lds_one = (size_t)(64 * vec1) * (4 * kb * bpb + 4);
-        break;
-      }
-    }
-  }
   return p;
 }
 
@@ -99,52 +80,65 @@ hipError_t launch_quant(const ColArgs& a, const ColPlan& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Single-pass launch; *done = false (and nothing launched) when the grid would not be
-// resident all at once.
+// Single-pass launch with KB blocks per wave; *done stays false (nothing launched) when
+// that grid would not be resident all at once or the lane would hold too many values.
 template <int N, int KIND, int KB>
-hipError_t launch_onepass_kb(const ColArgs& a, const ColPlan& p, hipStream_t s, int sq, bool* done) {
+hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
   constexpr int VEC = onepass_vec(N);
-  auto kern = col_quant_onepass_kernel<N, VEC, KIND, KB>;
-  static int per_cu = -1, cus = 0;   // per instantiation
-  if (per_cu < 0) {
-    int dev = 0, nb = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    // LDS of the largest tile this instantiation can be given (bpb <= N)
-    if (e == hipSuccess)
-      e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 256, (size_t)(64 * VEC) * (4 * KB * N + 4));
-    if (e != hipSuccess) return e;
-    per_cu = nb;
+  if constexpr (onepass_kept_regs<N, VEC, KIND, KB>() > kOnepassMaxKept) {
+    return hipSuccess;
+  } else {
+    if (*done || a.C % VEC != 0) return hipSuccess;
+    const int bpb = KIND == kKeepGeneric ? a.r : (KIND == kKeepAll8 ? N : N / 2);
+    const int64_t tiles = ceil_div(a.C, 64 * VEC) * ceil_div(a.R / N, 4 * KB);
+    size_t lds = (size_t)(64 * VEC) * (4 * KB * bpb + 4);
+    if (lds < onepass_stage_bytes<N, VEC, KIND>()) lds = onepass_stage_bytes<N, VEC, KIND>();
+    auto kern = col_quant_onepass_kernel<N, VEC, KIND, KB>;
+    constexpr size_t lds_tile_max = (size_t)(64 * VEC) * (4 * KB * N + 4);   // bpb <= N
+    constexpr size_t lds_max = lds_tile_max > onepass_stage_bytes<N, VEC, KIND>()
+                                   ? lds_tile_max : onepass_stage_bytes<N, VEC, KIND>();
+    static int per_cu = -1, cus = 0;   // per instantiation, for the LDS size last asked for
+    static size_t lds_seen = 0;
+    if (per_cu < 0 || lds != lds_seen) {
+      int dev = 0, nb = 0;
+      hipError_t e = hipGetDevice(&dev);
+      if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e == hipSuccess && per_cu < 0 && lds_max > 48 * 1024)
+        e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+      if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 256, lds);
+      if (e != hipSuccess) return e;
+      per_cu = nb;
+      lds_seen = lds;
+    }
+    if (tiles > (int64_t)per_cu * cus || tiles > kMaxPartials / 2) return hipSuccess;
+    const int wait_us = g_exchange_wait_us.load();
+    stage_begin(sq, s);
+    kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(
+        a.x, a.R, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
+        next_tag(), (long long)wait_us * 100, a.codes, a.pitch, a.scale);
+    stage_end(sq, s);
+    *done = true;
+    return hipGetLastError();
   }
-  if (p.tiles_one > (int64_t)per_cu * cus) return hipSuccess;
-  const int wait_us = g_exchange_wait_us.load();
-  stage_begin(sq, s);
-  kern<<<dim3((unsigned)p.tiles_one), dim3(256), p.lds_one, s>>>(
-      a.x, a.R, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
-      next_tag(), (long long)wait_us * 100, a.codes, a.pitch, a.scale);
-  stage_end(sq, s);
-  *done = true;
-  return hipGetLastError();
 }
 
+// The smallest number of blocks per wave (most workgroups, most loads in flight) whose grid
+// is resident at once; none fits a tensor whose kept values exceed the register files.
 template <int N, int KIND>
-hipError_t launch_onepass(const ColArgs& a, const ColPlan& p, hipStream_t s, int sq, bool* done) {
-  constexpr int VEC = onepass_vec(N);
-  if (p.kb_one == 1) return launch_onepass_kb<N, KIND, 1>(a, p, s, sq, done);
-  if constexpr (2 * VEC * N <= 96) {
-    if (p.kb_one == 2) return launch_onepass_kb<N, KIND, 2>(a, p, s, sq, done);
-  }
-  if constexpr (3 * VEC * N <= 96) {
-    if (p.kb_one == 3) return launch_onepass_kb<N, KIND, 3>(a, p, s, sq, done);
-  }
-  return hipSuccess;
+hipError_t launch_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
+  hipError_t e = hipSuccess;
+#define HOT_TRY_KB(KB) \
+  if (e == hipSuccess && !*done) e = try_onepass<N, KIND, KB>(a, s, sq, done);
+  HOT_TRY_KB(1) HOT_TRY_KB(2) HOT_TRY_KB(3) HOT_TRY_KB(5) HOT_TRY_KB(7) HOT_TRY_KB(10)
+#undef HOT_TRY_KB
+  return e;
 }
 
 template <int N, int KIND>
 hipError_t launch_nk(const ColArgs& a, const ColPlan& p, hipStream_t s, int sa, int sq) {
-  if (p.kb_one > 0 && g_exchange_wait_us.load() >= 0) {
+  if (g_exchange_wait_us.load() >= 0) {
     bool done = false;
-    const hipError_t e1 = launch_onepass<N, KIND>(a, p, s, sq, &done);
+    const hipError_t e1 = launch_onepass<N, KIND>(a, s, sq, &done);
     if (e1 != hipSuccess || done) return e1;
   }
   hipError_t e = hipErrorInvalidValue;

@@ -15,6 +15,8 @@
 // one partial maximum per workgroup; the quantise pass reduces them itself, so no
 // atomics and no zero-initialised memory are needed.
 #pragma once
+#include <type_traits>
+
 #include "hot_device.h"
 #include "hot_host.h"
 
@@ -167,6 +169,46 @@ __device__ __forceinline__ void fwht_even_rows(const float (&v)[N], float (&s)[N
 // compile time.
 template <int N, int KIND>
 constexpr int kept_vals() { return KIND == kKeepLowHalf ? N / 2 : N; }
+
+// The N rows of one block as loaded (zeros when `ok` is false; nothing is dereferenced
+// then).  `rows` is wave-uniform (the block's first row at the tile's first column), `col`
+// the lane's 32-bit column offset, so the row stride is added on the scalar unit.
+template <int N, int VEC>
+__device__ __forceinline__ void load_rows(const float* __restrict__ rows, int64_t C, uint32_t col,
+                                          bool ok, typename VecT<VEC>::type (&q)[N]) {
+  using VT = typename VecT<VEC>::type;
+#pragma unroll
+  for (int k = 0; k < N; ++k)
+    q[k] = ok ? *reinterpret_cast<const VT*>(rows + (int64_t)k * C + col) : VT{};
+}
+
+// Transform loaded rows into kept form (see load_block_kept).
+template <int N, int VEC, int KIND>
+__device__ __forceinline__ void transform_kept(const typename VecT<VEC>::type (&q)[N],
+                                               float (&v)[VEC][kept_vals<N, KIND>()]) {
+  if constexpr (KIND == kKeepLowHalf) {
+#pragma unroll
+    for (int j = 0; j < N / 2; ++j) {
+      float a[VEC], b[VEC];
+      unpack_vec<VEC>(q[2 * j], a);
+      unpack_vec<VEC>(q[2 * j + 1], b);
+#pragma unroll
+      for (int vi = 0; vi < VEC; ++vi) v[vi][j] = a[vi] + b[vi];
+    }
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) fwht_regs<N / 2>(v[vi]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      float o[VEC];
+      unpack_vec<VEC>(q[k], o);
+#pragma unroll
+      for (int vi = 0; vi < VEC; ++vi) v[vi][k] = o[vi];
+    }
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) fwht_regs<N>(v[vi]);
+  }
+}
 
 // Load one block and return its transformed values in kept form: all N natural rows, or
 // (kKeepLowHalf) the even natural rows, row 2j' at index j'.
@@ -330,8 +372,56 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
 // wall clock a workgroup computes the maxima still missing itself (each is a pure
 // function of that tile's input), so every wave finishes whether or not the other
 // workgroups are resident, and the result does not depend on who computed what.
+// Code bytes per block and column when the kept list is known at compile time.
+template <int N, int KIND>
+constexpr int static_bpb() { return KIND == kKeepAll8 ? N : N / 2; }
+
+// The codes of one column of a block (kept form) packed in output order.
+template <int N, int KIND, int ROUNDING>
+__device__ __forceinline__ void pack_kept_codes(const float (&v)[kept_vals<N, KIND>()], float inv,
+                                                uint32_t (&out)[static_bpb<N, KIND>() / 4]) {
+  static_assert(KIND != kKeepGeneric, "compile-time kept lists only");
+  if constexpr (KIND == kKeepAll4) {
+#pragma unroll
+    for (int k8 = 0; k8 < N / 8; ++k8) {
+      uint32_t d = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d |= (uint32_t)(quant_code(v[k8 * 8 + e], inv, 7, ROUNDING) & 0xF) << (4 * e);
+      out[k8] = d;
+    }
+  } else {
+#pragma unroll
+    for (int j4 = 0; j4 < static_bpb<N, KIND>() / 4; ++j4) {
+      uint32_t d = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j4 * 4 + e;
+        const int k = KIND == kKeepLowHalf ? (lowpass_row(N, j) >> 1) : j;
+        d |= (uint32_t)(quant_code(v[k], inv, 127, ROUNDING) & 0xFF) << (8 * e);
+      }
+      out[j4] = d;
+    }
+  }
+}
+
+// Register plan of the single-pass kernel: two waves share a SIMD (256 registers each);
+// a lane keeps KB * VEC * kept values for the whole kernel plus DEPTH row buffers of one
+// block (the next block's loads in flight under the current block's butterflies when that
+// still fits).
 template <int N, int VEC, int KIND, int KB>
-__global__ __launch_bounds__(256) void col_quant_onepass_kernel(
+constexpr int onepass_kept_regs() { return KB * VEC * kept_vals<N, KIND>(); }
+template <int N, int VEC, int KIND, int KB>
+constexpr int onepass_depth() { return (KB > 1 && onepass_kept_regs<N, VEC, KIND, KB>() + 2 * N * VEC <= 224) ? 2 : 1; }
+constexpr int kOnepassMaxKept = 160;
+
+// Bytes of dynamic LDS: the code tile, or (before the tile is filled) one column of
+// per-thread staging for the recomputation of another workgroup's maximum.
+template <int N, int VEC, int KIND>
+constexpr size_t onepass_stage_bytes() { return (size_t)kept_vals<N, KIND>() * 256 * VEC * 4; }
+
+template <int N, int VEC, int KIND, int KB>
+__global__ __launch_bounds__(256, 2)
+void col_quant_onepass_kernel(
     const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding,
     unsigned long long* __restrict__ slots, uint32_t tag, long long wait_ticks,
     uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scale) {
@@ -350,15 +440,47 @@ __global__ __launch_bounds__(256) void col_quant_onepass_kernel(
   const int64_t c0 = tx * CT + lane * VEC;
   const bool col_ok = c0 < C;
 
+  // Blocks one after the other, the next block's rows in flight under the current block's
+  // butterflies; only the kept values stay.
+  using VT = typename VecT<VEC>::type;
+  constexpr int DEPTH = onepass_depth<N, VEC, KIND, KB>();
   float v[KB][VEC][kept_vals<N, KIND>()];
   float m = 0.0f;
+  VT q[DEPTH][N];
+  const int64_t gb0 = ty * 4 * KB + __builtin_amdgcn_readfirstlane(w) * KB;
+  const float* tile_x = x + tx * CT;
+  uint32_t col = (uint32_t)lane * VEC;
+  if constexpr (DEPTH == 2)
+    load_rows<N, VEC>(tile_x + gb0 * N * C, C, col, gb0 < nblk && col_ok, q[0]);
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
-    const int64_t gb = ty * 4 * KB + w * KB + kb;
-    if (gb < nblk && col_ok) {
-      load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v[kb]);
-      m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v[kb], map));
+    VT(&cur)[N] = q[kb % DEPTH];
+    if constexpr (DEPTH == 2) {
+      if (kb + 1 < KB) {
+        const int64_t gn = gb0 + kb + 1;
+        load_rows<N, VEC>(tile_x + gn * N * C, C, col, gn < nblk && col_ok, q[(kb + 1) % 2]);
+      }
+    } else {
+      load_rows<N, VEC>(tile_x + (gb0 + kb) * N * C, C, col, gb0 + kb < nblk && col_ok, cur);
     }
+    transform_kept<N, VEC, KIND>(cur, v[kb]);   // zeros for a block past the end
+    m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v[kb], map));
+    // Pin the order: the column offset of every later load is made to depend (through an
+    // empty asm) on all finished values of this block, so the compiler can neither issue
+    // all the blocks' loads up front nor postpone the butterflies, both of which spill.
+#pragma unroll
+    for (int vi = 0; vi < VEC; ++vi) {
+      constexpr int NV = kept_vals<N, KIND>();
+      static_assert(NV % 8 == 0, "kept values per column");
+#pragma unroll
+      for (int j = 0; j < NV; j += 8) {
+        const float* t = &v[kb][vi][j];
+        asm volatile("" : "+v"(col)
+                     : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]), "v"(t[4]), "v"(t[5]), "v"(t[6]),
+                       "v"(t[7]));
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
   m = workgroup_max(m);
   if (tid == 0)
@@ -390,41 +512,113 @@ __global__ __launch_bounds__(256) void col_quant_onepass_kernel(
     }
   }
   __syncthreads();
-  if (s_nmiss > 0) {   // workgroup-uniform
+  if (s_nmiss > 0) {   // workgroup-uniform, rare
+    // Recompute the missing tiles' maxima with few registers: rows are read one (pair) at
+    // a time in a rolled loop and staged in this thread's own LDS column (the code tile is
+    // not in use yet), then transformed from there.
+    constexpr int NS = kept_vals<N, KIND>();
+    float* stage = reinterpret_cast<float*>(tile) + tid * VEC;
     for (int b = 0; b < (int)gridDim.x; ++b) {
       if (!((s_miss[b >> 5] >> (b & 31)) & 1u)) continue;
       const int64_t btx = b % tiles_x, bty = b / tiles_x;
       const int64_t bc0 = btx * CT + lane * VEC;
-      float mm = 0.0f;
+      if (bc0 >= C) continue;
       for (int kb = 0; kb < KB; ++kb) {
         const int64_t gb = bty * 4 * KB + w * KB + kb;
-        if (gb < nblk && bc0 < C) {
-          float t[VEC][kept_vals<N, KIND>()];
-          load_block_kept<N, VEC, KIND>(x + gb * N * C + bc0, C, t);
-          mm = fmaxf(mm, kept_form_absmax<N, VEC, KIND>(t, map));
+        if (gb >= nblk) break;
+        const float* src = x + gb * N * C + bc0;
+#pragma unroll 1
+        for (int j = 0; j < NS; ++j) {
+          float a[VEC];
+          if constexpr (KIND == kKeepLowHalf) {
+            float lo[VEC], hi[VEC];
+            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)(2 * j) * C), lo);
+            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)(2 * j + 1) * C), hi);
+#pragma unroll
+            for (int vi = 0; vi < VEC; ++vi) a[vi] = lo[vi] + hi[vi];
+          } else {
+            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)j * C), a);
+          }
+#pragma unroll
+          for (int vi = 0; vi < VEC; ++vi) stage[j * 256 * VEC + vi] = a[vi];
         }
+        float t[VEC][NS];
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+#pragma unroll
+          for (int vi = 0; vi < VEC; ++vi) t[vi][j] = stage[j * 256 * VEC + vi];
+        }
+#pragma unroll
+        for (int vi = 0; vi < VEC; ++vi) fwht_regs<NS>(t[vi]);
+        amax = fmaxf(amax, kept_form_absmax<N, VEC, KIND>(t, map));
       }
-      amax = fmaxf(amax, mm);
     }
+    __syncthreads();   // staging done before the tile is zeroed / filled
   }
   amax = workgroup_max(amax);
   const float inv = quant_inv(amax, QMAX);
   if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
 
-  // slots of blocks past the end must read back as zero codes
-  if ((ty + 1) * 4 * KB > nblk) {
-    for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
-    __syncthreads();
-  }
+  // A lane's codes of consecutive blocks are consecutive bytes of its column's output row:
+  // with enough of them (and a compile-time kept list) they are stored straight from
+  // registers, 16 or 8 bytes at a time; otherwise they go through the LDS tile.
+  constexpr bool kDirect = KIND != kKeepGeneric && static_bpb<N, KIND>() % 8 == 0 &&
+                           KB * static_bpb<N, KIND>() >= 64;
+  if constexpr (kDirect) {
+    constexpr int BPB = static_bpb<N, KIND>();
+    auto emit = [&](auto rounding_c) {
+      constexpr int ROUNDING = decltype(rounding_c)::value;
 #pragma unroll
-  for (int kb = 0; kb < KB; ++kb) {
-    const int slot = w * KB + kb;
-    const int64_t gb = ty * 4 * KB + slot;
-    if (gb < nblk && col_ok)
-      store_kept_form_codes<N, VEC, KIND>(v[kb], tile, lane, slot * bpb, TBP, map, inv, rounding);
+      for (int kb = 0; kb < KB; ++kb) {
+        const int slot = w * KB + kb;
+        const int64_t gb = ty * 4 * KB + slot;
+        if (gb < nblk && col_ok) {
+#pragma unroll
+          for (int vi = 0; vi < VEC; ++vi) {
+            uint32_t d[BPB / 4];
+            pack_kept_codes<N, KIND, ROUNDING>(v[kb][vi], inv, d);
+            uint8_t* dst = codes + (c0 + vi) * pitch + gb * BPB;
+            if constexpr (BPB % 16 == 0) {
+#pragma unroll
+              for (int i = 0; i < BPB / 16; ++i)
+                reinterpret_cast<uint4*>(dst)[i] = make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]);
+            } else {
+#pragma unroll
+              for (int i = 0; i < BPB / 8; ++i)
+                reinterpret_cast<uint2*>(dst)[i] = make_uint2(d[2 * i], d[2 * i + 1]);
+            }
+          }
+        }
+      }
+    };
+    if (rounding == 0) emit(std::integral_constant<int, 0>{});
+    else emit(std::integral_constant<int, 1>{});
+    // zero codes after the last block, up to the pitch (last row tile only)
+    if (ty == (nblk + 4 * KB - 1) / (4 * KB) - 1) {
+      const int64_t start = nblk * BPB;
+      const int pad_dw = (int)((pitch - start) >> 2);
+      for (int idx = tid; idx < CT * pad_dw; idx += 256) {
+        const int colx = idx / pad_dw, dw = idx - colx * pad_dw;
+        const int64_t c = tx * CT + colx;
+        if (c < C) *reinterpret_cast<uint32_t*>(codes + c * pitch + start + 4 * dw) = 0u;
+      }
+    }
+  } else {
+    // slots of blocks past the end must read back as zero codes
+    if ((ty + 1) * 4 * KB > nblk) {
+      for (int i = tid; i < CT * TBP / 4; i += 256) reinterpret_cast<uint32_t*>(tile)[i] = 0u;
+      __syncthreads();
+    }
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      const int slot = w * KB + kb;
+      const int64_t gb = ty * 4 * KB + slot;
+      if (gb < nblk && col_ok)
+        store_kept_form_codes<N, VEC, KIND>(v[kb], tile, lane, slot * bpb, TBP, map, inv, rounding);
+    }
+    __syncthreads();
+    write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, KB, C, pitch, codes);
   }
-  __syncthreads();
-  write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, KB, C, pitch, codes);
 }
 
 // Columns per lane of the single-pass kernel: two for 16-row blocks, else one.
@@ -433,9 +627,6 @@ __host__ __device__ constexpr int onepass_vec(int n) { return n == 16 ? 2 : 1; }
 // Host-side launch parameters shared by the two passes.
 struct ColPlan {
   int kind;
-  int kb_one;           // > 0: single-pass kernel with this many blocks per wave
-  int64_t tiles_one;
-  size_t lds_one;
   int vec_a, kbw_a;     // abs-max pass: wide loads, few registers beyond the block itself
   int absmax_grid;
   int vec_q, kbw_q;     // quantise pass: narrow tiles, more waves in flight
