@@ -563,7 +563,7 @@ void col_quant_onepass_kernel(
   // with enough of them (and a compile-time kept list) they are stored straight from
   // registers, 16 or 8 bytes at a time; otherwise they go through the LDS tile.
   constexpr bool kDirect = KIND != kKeepGeneric && static_bpb<N, KIND>() % 8 == 0 &&
-                           KB * static_bpb<N, KIND>() >= 64;
+                           KB * static_bpb<N, KIND>() >= 48;
   if constexpr (kDirect) {
     constexpr int BPB = static_bpb<N, KIND>();
     auto emit = [&](auto rounding_c) {
