@@ -218,3 +218,39 @@ def exact_backward(g_y, x, w, want_gx: bool = True, want_gw: bool = True):
     g_w = np.empty((O, I), dtype=np.float64) if want_gw else None
     lib().hot_oracle_exact_backward(_p(g_y), _p(x), _p(w), i64(L), i64(O), i64(I), _p(g_x), _p(g_w))
     return g_x, g_w
+
+
+# ---- bf16 variant of the weight-gradient path (Sec. 4.2 finds g_w the path that is
+# sensitive to quantisation; the low-rank projection is kept, the integer quantiser is
+# replaced by bfloat16 operands with a wide accumulator) ---------------------------------
+
+def bf16_bits(a) -> np.ndarray:
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest, ties to even.
+    bfloat16 is the upper half of the fp32 pattern: add half an ulp of the kept part,
+    plus its last bit for the tie rule, and truncate.  Inputs must be finite."""
+    u = _f32(a).view(np.uint32).astype(np.uint64)
+    kept_lsb = (u >> 16) & 1
+    return ((u + 0x7FFF + kept_lsb) >> 16).astype(np.uint16)
+
+
+def bf16_value(bits) -> np.ndarray:
+    """bfloat16 bit patterns -> the fp32 values they denote."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def compress_activation_bf16(x, n: int, r: int, keep=None) -> np.ndarray:
+    """HLA(x) along the tokens (same transform as compress_activation), stored as bfloat16:
+    returns the bit patterns [L*r/n, I] (uint16)."""
+    keep = lowpass_index(n, r) if keep is None else _i32(keep)
+    return bf16_bits(hla(x, n, r, keep))
+
+
+def backward_gw_bf16(g_y, x_bits, n: int, r: int, keep=None):
+    """g_w = HLA(g_y)^T . x_hat / n with both operands rounded to bfloat16 and the sum in
+    double (a product of two bfloat16 values is exact in double).
+    Returns dict(g_w [O, I] float64, gh_bits [L*r/n, O] uint16)."""
+    keep = lowpass_index(n, r) if keep is None else _i32(keep)
+    gh_bits = bf16_bits(hla(g_y, n, r, keep))
+    A = bf16_value(gh_bits).astype(np.float64)
+    B = bf16_value(x_bits).astype(np.float64)
+    return dict(g_w=(A.T @ B) / float(n), gh_bits=gh_bits)

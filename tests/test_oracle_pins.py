@@ -332,3 +332,57 @@ def test_select_quantizer_mse_in_original_domain_and_end_points():
     assert choice and m_tok < 0.5 * m_ten
     # all-zero gradient: nothing to gain
     assert oracle.select_quantizer(np.zeros((L, O), np.float32), n)[0] is False
+
+
+# ---- bf16 variant of the g_w path ---------------------------------------------------------
+
+def test_bf16_rounding_matches_an_independent_conversion_and_the_tie_rule():
+    import torch
+    rng = np.random.default_rng(11)
+    a = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 10.0 ** rng.integers(-20, 20, 20000),
+                        np.array([0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-40], dtype=np.float32)])
+    mine = oracle.bf16_bits(a)
+    theirs = torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(mine, theirs)
+    # exact ties: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> even (1); 1 + 3*2^-8 -> 1 + 2^-6
+    ties = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8)], dtype=np.float32)
+    assert np.array_equal(oracle.bf16_value(oracle.bf16_bits(ties)),
+                          np.array([1.0, 1.0 + 2.0 ** -6, -1.0], dtype=np.float32))
+    # values already representable are untouched
+    exact = np.array([0.5, -2.75, 96.0, 2.0 ** -100], dtype=np.float32)
+    assert np.array_equal(oracle.bf16_value(oracle.bf16_bits(exact)), exact)
+
+
+def test_bf16_gw_is_the_exact_product_of_its_rounded_operands_and_close_to_hla():
+    rng = np.random.default_rng(12)
+    L, O, I, n, r = 128, 24, 20, 16, 8
+    gy = (rng.standard_normal((L, O)) * 1e-3).astype(np.float32)
+    x = rng.standard_normal((L, I)).astype(np.float32)
+    xb = oracle.compress_activation_bf16(x, n, r)
+    out = oracle.backward_gw_bf16(gy, xb, n, r)
+    keep = oracle.lowpass_index(n, r)
+    gh = oracle.hla(gy, n, r, keep).astype(np.float64)
+    xh = oracle.hla(x, n, r, keep).astype(np.float64)
+    # brute force over the rounded operands, term by term
+    A, B = oracle.bf16_value(out["gh_bits"]).astype(np.float64), oracle.bf16_value(xb).astype(np.float64)
+    brute = np.zeros((O, I))
+    for k in range(A.shape[0]):
+        brute += np.outer(A[k], B[k])
+    np.testing.assert_allclose(out["g_w"], brute / n, rtol=1e-12, atol=1e-18)
+    # each operand is within 2^-9 relative of the unrounded one, so every term is within
+    # ~2^-8 and the result within 2^-8 * sum |terms|
+    bound = 2.0 ** -8 * (np.abs(gh).T @ np.abs(xh)) / n + 1e-30
+    assert (np.abs(out["g_w"] - gh.T @ xh / n) <= bound).all()
+
+
+def test_bf16_gw_full_rank_reproduces_the_exact_gradient_for_bf16_exact_inputs():
+    """r = n and inputs whose transformed values are exactly representable in bfloat16
+    (small integers): the reduced-rank bf16 path is then the exact g_y^T x."""
+    rng = np.random.default_rng(13)
+    L, O, I, n = 64, 8, 6, 16
+    gy = rng.integers(-3, 4, size=(L, O)).astype(np.float32)
+    x = rng.integers(-3, 4, size=(L, I)).astype(np.float32)
+    keep = np.arange(n, dtype=np.int32)
+    xb = oracle.compress_activation_bf16(x, n, n, keep)
+    out = oracle.backward_gw_bf16(gy, xb, n, n, keep)
+    assert np.array_equal(out["g_w"], gy.astype(np.float64).T @ x.astype(np.float64))
