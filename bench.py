@@ -20,27 +20,30 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA
+BF16_PEAK_TOPS = 2500.0     # MI355X dense bf16 MFMA (gw_bits = 16 variant)
 
 
-def stage_model(L, O, I, n, r, gx_bits, per_token):
+def stage_model(L, O, I, n, r, gx_bits, per_token, gw_bits=8):
     """Algorithmic work per launch of every kernel role: HBM bytes for the
     transform/quantise kernels, integer ops (and compulsory bytes) for the GEMMs."""
     Lr = L // n * r
     cb = gx_bits / 8.0
+    wb = gw_bits / 8.0
     m = {
         "act_col_absmax": dict(bound="hbm", bytes=4 * L * I),
-        "act_col_quant": dict(bound="hbm", bytes=4 * L * I + Lr * I),
+        "act_col_quant": dict(bound="hbm", bytes=4 * L * I + wb * Lr * I),
         "w_col_absmax": dict(bound="hbm", bytes=4 * O * I),
         "w_col_quant": dict(bound="hbm", bytes=4 * O * I + cb * O * I),
         "gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L),
         "gy_row_absmax": dict(bound="hbm", bytes=4 * L * O),
         "gy_row_quant2": dict(bound="hbm", bytes=4 * L * O + cb * L * O),
         "gyT_col_absmax": dict(bound="hbm", bytes=4 * L * O),
-        "gyT_col_quant": dict(bound="hbm", bytes=4 * L * O + Lr * O),
+        "gyT_col_quant": dict(bound="hbm", bytes=4 * L * O + wb * Lr * O),
         "gy_fused_absmax": dict(bound="hbm", bytes=4 * L * O + (4 * L * ((O + 127) // 128) if per_token else 0)),
         "gy_fused_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + Lr * O + 4 * L),
         "gx_igemm": dict(bound="mfma", ops=2 * L * O * I, bytes=cb * (L * O + I * O) + 4 * L * I),
-        "gw_igemm": dict(bound="mfma", ops=2 * O * I * Lr, bytes=Lr * (O + I) + 4 * O * I),
+        "gw_igemm": dict(bound="mfma", ops=2 * O * I * Lr, bytes=wb * Lr * (O + I) + 4 * O * I,
+                         peak=BF16_PEAK_TOPS if gw_bits == 16 else INT8_PEAK_TOPS),
     }
     return m
 
@@ -177,6 +180,8 @@ def main() -> int:
     ap.add_argument("--probe-peaks", action="store_true",
                     help="instead of the workload, time plain HBM read/write and a register-only "
                          "int8 matrix loop, and print them as JSON")
+    ap.add_argument("--gw-bits", type=int, default=8, choices=[8, 16],
+                    help="g_w operands: 8 = INT8 (the paper), 16 = bfloat16 variant")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the timed step, run every layer of the workload once (compress "
                          "all, then backward all; chained where the workload is a chain) and print "
@@ -207,7 +212,7 @@ def main() -> int:
     L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep
     quant = args.quantizer or ("token" if wl.quantizer in ("token", "select") else "tensor")
     per_token = quant == "token"
-    cfg = hot.Config(block=n, keep=r)
+    cfg = hot.Config(block=n, keep=r, gw_bits=args.gw_bits)
 
     x, w, gy = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
     ws = hot.alloc_workspace(cfg, L, O, I)
@@ -248,7 +253,7 @@ def main() -> int:
     torch.cuda.synchronize()
     prof = hot.hot_debug_profile_end()
 
-    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token)
+    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token, cfg.gw_bits)
     kernels = {}
     for name, (ms, cnt) in prof.items():
         avg_us = ms * 1e3 / cnt
@@ -267,11 +272,12 @@ def main() -> int:
                     frac=round(d["GBps"] / HBM_PEAK_GBS, 4), traffic=None,
                     algorithmic_bytes=int(dm["bytes"]), avg_us=d["avg_us"])
     else:
-        roof = dict(kernel=dominant, bound="mfma", achieved=d["TOPS"], peak=INT8_PEAK_TOPS, unit="TOP/s",
-                    frac=round(d["TOPS"] / INT8_PEAK_TOPS, 4), traffic=None,
+        peak = dm.get("peak", INT8_PEAK_TOPS)
+        roof = dict(kernel=dominant, bound="mfma", achieved=d["TOPS"], peak=peak, unit="TOP/s",
+                    frac=round(d["TOPS"] / peak, 4), traffic=None,
                     algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
 
-    if quant == "token" and not args.one_call:   # the configuration the counter runs measured
+    if quant == "token" and not args.one_call and args.gw_bits == 8:   # what the counter runs measured
         roof["traffic"] = profiled_traffic(wl.name, dominant)
     Lr = L // n * r
     ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
@@ -286,9 +292,12 @@ def main() -> int:
         reps, dt = 0, 0.0
         while reps < 1 or (dt < args.cpu_seconds and reps < 64):
             t0 = time.perf_counter()
-            codes, sx = oracle.compress_activation(xs, n, r)
             oracle.backward_gx(gys, wh, n, bits=cfg.gx_bits, per_token=per_token, taps=False)
-            oracle.backward_gw(gys, codes, sx, n, r, taps=False)
+            if cfg.gw_bits == 16:
+                oracle.backward_gw_bf16(gys, oracle.compress_activation_bf16(xs, n, r), n, r)
+            else:
+                codes, sx = oracle.compress_activation(xs, n, r)
+                oracle.backward_gw(gys, codes, sx, n, r, taps=False)
             dt += time.perf_counter() - t0
             reps += 1
         ops_s = 2 * Ls * O * I + 2 * O * I * (Ls // n * r)
@@ -301,7 +310,7 @@ def main() -> int:
         "metric": "HOT linear-backward effective TOPS (integer ops executed / step time)",
         "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8" if cfg.gw_bits == 8 else "int8 (g_x) + bf16 (g_w)",
         "data": "synthetic",
         "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
                    "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,

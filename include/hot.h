@@ -58,7 +58,7 @@ typedef struct {
                               NULL = the r rows of lowest sequency, by increasing
                               sequency (Sec. 3.3)                                     */
   int32_t gx_bits;         /* 4 (paper, Sec. 5.1) | 8 (INT8 warm-up, Supp. B)         */
-  int32_t gw_bits;         /* 8 (Sec. 5.2)                                            */
+  int32_t gw_bits;         /* 8 (Sec. 5.2) | 16: bfloat16 operands, fp32 accumulation   */
   int32_t rounding;        /* hot_rounding                                            */
   float lqs_threshold;     /* 0.5 (Sec. 5.2.2)                                        */
 } hot_config;
@@ -121,6 +121,10 @@ hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y
 /*
  * Weight-gradient path, Sec. 5.2 (Eq. 5 with INT8 operands):
  *   g_w = dequant( Q(HLA(g_y))^T . x_hat ),  HLA along the token index L.
+ * With gw_bits = 16 (g_w is the gradient Sec. 4.2 finds sensitive to quantisation) the two
+ * low-rank operands are rounded to bfloat16 instead (nearest even, no scales; the
+ * activation buffer is then 25 % of fp32), multiplied on the bf16 matrix cores with fp32
+ * accumulation and divided by n; no limit on L*r/n.
  * g_y: device [L x O] (in); act_buf: what hot_compress_activation wrote for the
  * same cfg, L, I (in); g_w: device [O x I] (out).  Requires L % n == 0.
  */
@@ -156,7 +160,9 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
 
 /* ---- parity views (not on the timed path): logical forms of packed data ---- */
 
-/* Compressed activation as row-major codes [L*r/n x I] and its scale [1]. */
+/* Compressed activation as row-major codes [L*r/n x I] and its scale [1].  With
+ * gw_bits = 16 `codes` receives bfloat16 bit patterns, two bytes each (pass an int16
+ * buffer), and the scale is 1. */
 hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_buf, int64_t L,
                                        int64_t I, int8_t* codes, float* scale, void* stream);
 
@@ -176,7 +182,9 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t 
 
 /* Operands left in `ws` by the last hot_linear_backward_gw: codes of HLA(g_y)
  * [L*r/n x O] row-major, its scale [1], and the int32 product [O x I] recomputed
- * from those codes and act_buf.  Any output may be NULL. */
+ * from those codes and act_buf.  Any output may be NULL.  With gw_bits = 16 the codes are
+ * bfloat16 bit patterns (two bytes each) and `acc` receives the fp32 accumulators' bit
+ * patterns. */
 hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const void* act_buf,
                                  int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
                                  float* gy_scale, int32_t* acc, void* stream);

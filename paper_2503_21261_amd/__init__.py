@@ -269,9 +269,11 @@ def hot_select_quantizer(cfg: Config, g_y: torch.Tensor, ws: torch.Tensor,
 
 
 def hot_debug_unpack_activation(cfg: Config, act_buf: torch.Tensor, L: int, I: int, stream=None):
-    """Returns (codes int8 [L*r/n, I], scale float32 [1]) on the device."""
+    """Returns (codes int8 [L*r/n, I], scale float32 [1]) on the device; with gw_bits = 16
+    the codes are bfloat16 bit patterns (int16) and the scale is 1."""
     Lr = L // cfg.block * cfg.keep
-    codes = torch.empty((Lr, I), dtype=torch.int8, device=act_buf.device)
+    codes = torch.empty((Lr, I), dtype=torch.int16 if cfg.gw_bits == 16 else torch.int8,
+                        device=act_buf.device)
     scale = torch.empty(1, dtype=torch.float32, device=act_buf.device)
     st = lib().hot_debug_unpack_activation(C.byref(cfg.c()), _ptr(act_buf), L, I, _ptr(codes),
                                            _ptr(scale), _stream(stream))
@@ -297,15 +299,18 @@ def hot_debug_gx_operands(cfg: Config, ws: torch.Tensor, L: int, O: int, I: int,
 
 def hot_debug_gw_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, L: int, O: int,
                           I: int, want_acc: bool = True, stream=None):
-    """Returns dict(qg [L*r/n,O] int8, sg [1], acc [O,I] int32)."""
+    """Returns dict(qg [L*r/n,O] int8, sg [1], acc [O,I] int32); with gw_bits = 16 qg holds
+    bfloat16 bit patterns (int16) and acc the fp32 accumulators (float32)."""
     dev = ws.device
     Lr = L // cfg.block * cfg.keep
-    qg = torch.empty((Lr, O), dtype=torch.int8, device=dev)
+    qg = torch.empty((Lr, O), dtype=torch.int16 if cfg.gw_bits == 16 else torch.int8, device=dev)
     sg = torch.empty(1, dtype=torch.float32, device=dev)
     acc = torch.empty((O, I), dtype=torch.int32, device=dev) if want_acc else None
     st = lib().hot_debug_gw_operands(C.byref(cfg.c()), _ptr(ws), _ptr(act_buf), L, O, I, _ptr(qg),
                                      _ptr(sg), _ptr(acc), _stream(stream))
     _check(st, "hot_debug_gw_operands")
+    if acc is not None and cfg.gw_bits == 16:
+        acc = acc.view(torch.float32)
     return dict(qg=qg, sg=sg, acc=acc)
 
 

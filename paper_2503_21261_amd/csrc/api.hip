@@ -30,7 +30,7 @@ hot_status resolve_config(const hot_config* cfg, Config* out) {
   if (n != 16 && n != 32 && n != 64) return HOT_ERR_ARG;
   if (r < 1 || r > n) return HOT_ERR_ARG;
   if (cfg->gx_bits != 4 && cfg->gx_bits != 8) return HOT_ERR_ARG;
-  if (cfg->gw_bits != 8) return HOT_ERR_ARG;
+  if (cfg->gw_bits != 8 && cfg->gw_bits != 16) return HOT_ERR_ARG;
   if (cfg->rounding != HOT_ROUND_NEAREST_EVEN && cfg->rounding != HOT_ROUND_PSEUDO_STOCHASTIC)
     return HOT_ERR_ARG;
   if (!(cfg->lqs_threshold >= 0.0f)) return HOT_ERR_ARG;
@@ -72,8 +72,8 @@ GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
 GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GwLayout g;
   g.Lr = L / c.n * c.r;
-  g.pitch = round_up(g.Lr, kPitchAlign);
-  g.plan = plan_gemm(O, I, g.pitch, c.gw_bits, true);
+  g.pitch = round_up(g.Lr * (c.gw_bits / 8), kPitchAlign);
+  g.plan = plan_gemm(O, I, g.pitch, c.gw_bits, c.gw_bits == 8);
   g.scalars = 0;
   g.qg = kWsPrefix;
   g.partial = g.qg + (size_t)round_up(O * g.pitch, 256);
@@ -113,7 +113,7 @@ WeightLayout weight_layout(const Config& c, int64_t O, int64_t I) {
 ActLayout act_layout(const Config& c, int64_t L, int64_t I) {
   ActLayout a;
   a.Lr = L / c.n * c.r;
-  a.pitch = round_up(a.Lr, kPitchAlign);
+  a.pitch = round_up(a.Lr * (c.gw_bits / 8), kPitchAlign);
   a.codes = kHeaderBytes;
   a.total = a.codes + (size_t)(I * a.pitch);
   return a;
@@ -126,7 +126,9 @@ bool gx_shape_ok(const Config& c, int64_t L, int64_t O, int64_t I) {
          O <= (c.gx_bits == 4 ? kMaxK4 : kMaxK8);
 }
 bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
-  return cols >= 1 && L >= c.n && L % c.n == 0 && L / c.n * c.r <= kMaxK8 && cols < (1ll << 31);
+  // the int32 bound on L' only binds integer accumulators; bfloat16 operands sum in fp32
+  return cols >= 1 && L >= c.n && L % c.n == 0 && cols < (1ll << 31) && L < (1ll << 31) &&
+         (c.gw_bits == 16 || L / c.n * c.r <= kMaxK8);
 }
 
 KeepMap identity_map(int n) {
@@ -217,6 +219,10 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   const ActLayout a = act_layout(c, L, I);
   uint8_t* base = (uint8_t*)act_buf;
   float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
+  if (c.gw_bits == 16) {
+    HOT_TRY(launch_col_bf16(x, L, I, c, base + a.codes, a.pitch, (float*)base, s, kStActQuant));
+    return HOT_OK;
+  }
   HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, false, c.gw_bits, base + a.codes, a.pitch,
                            (float*)base, partials, s, kStActAbsmax, kStActQuant));
   return HOT_OK;
@@ -335,8 +341,11 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   const uint8_t* abase = (const uint8_t*)act_buf;
 
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
-  HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
-                           kStGyTAbsmax, kStGyTQuant));
+  if (c.gw_bits == 16)
+    HOT_TRY(launch_col_bf16(g_y, L, O, c, qg, g.pitch, s_g, s, kStGyTQuant));
+  else
+    HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
+                             kStGyTAbsmax, kStGyTQuant));
   HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.plan, partial,
                        nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
   return HOT_OK;
@@ -354,7 +363,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c)) {
+  if (!gy_fused_supported(c) || c.gw_bits == 16) {
     st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
     if (st != HOT_OK) return st;
     return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
@@ -432,7 +441,7 @@ hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_bu
   const ActLayout a = act_layout(c, L, I);
   hipStream_t s = (hipStream_t)stream;
   const uint8_t* base = (const uint8_t*)act_buf;
-  if (codes) HOT_TRY(launch_unpack(base + a.codes, I, a.Lr, a.pitch, 8, 1, codes, s));
+  if (codes) HOT_TRY(launch_unpack(base + a.codes, I, a.Lr, a.pitch, c.gw_bits, 1, codes, s));
   if (scale) HOT_TRY(hipMemcpyAsync(scale, base, 4, hipMemcpyDeviceToDevice, s));
   return HOT_OK;
 }
@@ -494,12 +503,12 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
   const ActLayout a = act_layout(c, L, I);
   hipStream_t s = (hipStream_t)stream;
   const uint8_t* base = (const uint8_t*)ws;
-  if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, 8, 1, gy_codes, s));
+  if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, c.gw_bits, 1, gy_codes, s));
   if (gy_scale) HOT_TRY(hipMemcpyAsync(gy_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch, 8,
-                         plan_gemm(O, I, g.pitch, 8, false), nullptr, acc, nullptr, nullptr, 0,
-                         nullptr, c.n, s));
+    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch,
+                         c.gw_bits, plan_gemm(O, I, g.pitch, c.gw_bits, false), nullptr, acc, nullptr,
+                         nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
 
@@ -513,7 +522,7 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const
   if (st != HOT_OK) return st;
   if (!ws || (acc_gw && !act_buf)) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c)) return HOT_ERR_UNIMPLEMENTED;
+  if (!gy_fused_supported(c) || c.gw_bits == 16) return HOT_ERR_UNIMPLEMENTED;
   st = hot_debug_gx_operands(cfg, ws, L, O, I, gy_quantizer, gy_codes, gy_scales, w_codes, w_scale,
                              acc_gx, stream);
   if (st != HOT_OK) return st;

@@ -132,6 +132,11 @@ hipError_t launch_gy_fused(const float* g_y, int64_t L, int64_t O, const Config&
                            float* s_gh, float* part_hla, float* part_row, float* rowpart,
                            hipStream_t s, int stage_absmax, int stage_quant);
 
+// bfloat16 form of the same transposed low-rank operand (g_w path with gw_bits = 16):
+// out row c holds the kept values of column c as bfloat16; *scale is set to 1.
+hipError_t launch_col_bf16(const float* x, int64_t R, int64_t C, const Config& cfg, uint8_t* out,
+                           int64_t pitch, float* scale, hipStream_t s, int stage);
+
 // Bounded wait of the single-pass column kernel (microseconds; < 0: always two passes).
 void set_exchange_wait_us(int us);
 

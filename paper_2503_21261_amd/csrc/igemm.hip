@@ -11,6 +11,11 @@ __global__ void unpack_kernel(const uint8_t* __restrict__ codes, int64_t rows, i
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
        i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t row = i / K, k = i - row * K;
+    if (bits == 16) {   // two-byte elements (bfloat16 patterns) in, two-byte elements out
+      reinterpret_cast<uint16_t*>(out)[transpose ? k * rows + row : i] =
+          *reinterpret_cast<const uint16_t*>(codes + row * pitch + 2 * k);
+      continue;
+    }
     int c;
     if (bits == 4) {
       const int byte = codes[row * pitch + (k >> 1)];
@@ -83,14 +88,15 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_s
 
 namespace {
 
-template <int BM, int BN, int BKB, bool INT4>
+template <int BM, int BN, int BKB, bool INT4, bool BF16 = false>
 hipError_t launch_tile(GemmArgs g, int64_t k_bytes, hipStream_t s, int gemm_stage, int reduce_stage) {
+  if (BF16 && g.split != 1) return hipErrorInvalidValue;
   g.nk_total = (int)(k_bytes / BKB);
   g.stages_per_split = (int)ceil_div(g.nk_total, g.split);
   g.tiles_m = (int)ceil_div(g.M, BM);
   g.tiles_n = (int)ceil_div(g.N, BN);
   const size_t lds = 2 * (size_t)(BM + BN) * BKB;
-  auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4>;
+  auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4, BF16>;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -134,6 +140,11 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   g.col_scale = col_scale;
   g.inv_n = 1.0f / (float)n;
   const int gs = gemm_stage, rs = reduce_stage;
+  if (bits == 16) {
+    if (plan.bm == 256) return launch_tile<256, 256, 128, false, true>(g, k_bytes, s, gs, rs);
+    if (plan.bm == 128) return launch_tile<128, 128, 128, false, true>(g, k_bytes, s, gs, rs);
+    return hipErrorInvalidValue;
+  }
   if (plan.bm == 256)
     return bits == 4 ? launch_tile<256, 256, 64, true>(g, k_bytes, s, gs, rs)
                      : launch_tile<256, 256, 128, false>(g, k_bytes, s, gs, rs);

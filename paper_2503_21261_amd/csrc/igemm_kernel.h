@@ -24,6 +24,8 @@ namespace hot {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // Compile-time loop: f(std::integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
 template <int... Is, class F>
@@ -92,8 +94,13 @@ struct Operands {            // what the matrix instructions of one K slice cons
   v4i b[INT4 ? 2 : 1][TN];
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, bool INT4>
+// BF16 = true: the same data movement with bfloat16 operands (16 bytes per lane are 8
+// elements of v_mfma_f32_32x32x16_bf16) and fp32 accumulators; the "integer" outputs then
+// carry the accumulators' fp32 bit patterns, and K cannot be split.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, bool INT4, bool BF16 = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const GemmArgs g) {
+  static_assert(!(INT4 && BF16), "one operand format");
+  using acc_t = std::conditional_t<BF16, v16f, v16i>;
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
       *reinterpret_cast<v4i*>(&Bs[buf * BN * LP + RPP * p * LP + st_off]) = rb[p];
   };
 
-  v16i acc[TM][TN];
+  acc_t acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -258,7 +265,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
         }
       });
       constexpr int h = q / (TM * TN), i = (q % (TM * TN)) / TN, j = q % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(uc.a[h][i], uc.b[h][j], acc[i][j], 0, 0, 0);
+      if constexpr (BF16)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, uc.a[h][i]),
+                                                            __builtin_bit_cast(v8bf, uc.b[h][j]),
+                                                            acc[i][j], 0, 0, 0);
+      else
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(uc.a[h][i], uc.b[h][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     });
   };
@@ -295,7 +307,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          mine[((i * TN + j) * 16 + v) * NT + tid] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
+          if constexpr (!BF16)
+            mine[((i * TN + j) * 16 + v) * NT + tid] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
     return;
   }
 
@@ -331,7 +344,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
         const int row_off = ml * g.N + nl0;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          if (n0 + nl0 + j * 32 < g.N) obase[row_off + j * 32] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
+          if (n0 + nl0 + j * 32 < g.N) {
+            if constexpr (BF16) obase[row_off + j * 32] = __float_as_int(acc[i][j][v]);
+            else obase[row_off + j * 32] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
+          }
       }
     }
   }

@@ -48,6 +48,16 @@ def test_act_buffer_is_one_eighth_of_fp32():
     assert hot.hot_act_buffer_bytes(hot.Config(block=24), 480, 768) == 0
 
 
+def test_bf16_activation_buffer_is_a_quarter_of_fp32():
+    cfg = hot.Config(block=32, keep=16, gw_bits=16)
+    L, I = 12608, 768
+    assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((L + 127) // 128 * 128)
+    # no int32 bound on the reduction length with fp32 accumulation
+    assert hot.hot_act_buffer_bytes(hot.Config(gw_bits=16), 16 * 2 * 140000, 8) > 0
+    assert hot.hot_act_buffer_bytes(hot.Config(gw_bits=8), 16 * 2 * 140000, 8) == 0
+    assert hot.hot_workspace_bytes(hot.Config(gw_bits=12), 64, 64, 64) == 0
+
+
 def test_weight_buffer_is_a_header_plus_padded_code_rows():
     assert hot.hot_weight_buffer_bytes(hot.Config(), 768, 768) == 256 + 768 * 384
     assert hot.hot_weight_buffer_bytes(hot.Config(gx_bits=8), 144, 10) == 256 + 10 * 256

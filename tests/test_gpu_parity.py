@@ -618,3 +618,66 @@ def test_gw_longest_reduction_with_saturated_codes():
     cfg = hot.Config(block=n, keep=r)
     ref, gw = check_gw(hot, cfg, gy, x, "longest L'")
     assert (ref["qg"] == 127).all() and (ref["acc"] == 127 * 127 * Lr).all()
+
+
+# ---- bfloat16 variant of the g_w path (gw_bits = 16) ----------------------------------------
+
+def check_gw_bf16(hot, cfg, gy, x, what):
+    """Operand bit patterns must be identical; fp32 accumulators and g_w within 1e-5 of the
+    oracle's double-precision sum of the same bf16 products (max-norm)."""
+    L, O = gy.shape
+    I = x.shape[1]
+    n, r = cfg.block, cfg.keep
+    _say(f"[gw bf16] {what} L={L} O={O} I={I} n={n} r={r} keep={cfg.keep_idx}")
+    keep = None if cfg.keep_idx is None else list(cfg.keep_idx)
+    xb_ref = oracle.compress_activation_bf16(x.numpy(), n, r, keep)
+    ref = oracle.backward_gw_bf16(gy.numpy(), xb_ref, n, r, keep)
+    gyd, xd = gy.cuda(), x.cuda()
+    act = hot.alloc_act_buffer(cfg, L, I)
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    ws.fill_(0x5A)
+    hot.hot_compress_activation(cfg, xd, act, ws)
+    codes, sx = hot.hot_debug_unpack_activation(cfg, act, L, I)
+    gw = torch.empty((O, I), dtype=torch.float32, device="cuda")
+    hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
+    taps = hot.hot_debug_gw_operands(cfg, ws, act, L, O, I)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy().view(np.uint16), xb_ref), f"{what}: bf16 activation differs"
+    assert np.array_equal(taps["qg"].cpu().numpy().view(np.uint16), ref["gh_bits"]), f"{what}: bf16 HLA(g_y) differs"
+    assert sx.item() == 1.0 and taps["sg"].item() == 1.0
+    assert_close_maxnorm(taps["acc"].cpu().numpy(), ref["g_w"] * n, what + " accumulators")
+    assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w")
+    Lr = L // n * r
+    assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((2 * Lr + 127) // 128 * 128)
+    return ref, gw
+
+
+@pytest.mark.parametrize("case", [(16, 8, 4, 16, 8, None), (272, 130, 72, 16, 8, None),
+                                  (512, 200, 136, 32, 16, None), (1024, 96, 260, 64, 32, None),
+                                  (240, 64, 72, 16, 3, None), (256, 64, 64, 16, 4, [5, 0, 9, 14]),
+                                  (256, 64, 64, 16, 16, None), (4096, 300, 140, 16, 8, None)])
+def test_gw_bf16_small_shapes(case):
+    L, O, I, n, r, keep_idx = case
+    hot = _hot()
+    x, w, gy = make(L, O, I, seed=51, gy_kind="t4")
+    check_gw_bf16(hot, hot.Config(block=n, keep=r, keep_idx=keep_idx, gw_bits=16), gy, x, "bf16 small")
+
+
+def test_gw_bf16_config2_full_size():
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg2_vitb_fc1"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep, gw_bits=16)
+    ref, gw = check_gw_bf16(hot, cfg, gy, x, "bf16 cfg2")
+    _, exact = oracle.exact_backward(gy.numpy(), x.numpy(), w.numpy(), want_gx=False)
+    rel = np.linalg.norm(gw.cpu().numpy() - exact) / np.linalg.norm(exact)
+    _say(f"cfg2 bf16 g_w relative Frobenius error vs exact backward (statistic): {rel:.4f}")
+    # the one-call form takes the same path for its g_w half
+    gx = torch.empty((gy.shape[0], w.shape[1]), device="cuda")
+    gw2 = torch.empty_like(gw)
+    ws = hot.alloc_workspace(cfg, *gy.shape, w.shape[1])
+    act = hot.alloc_act_buffer(cfg, gy.shape[0], x.shape[1])
+    hot.hot_compress_activation(cfg, x.cuda(), act, ws)
+    hot.hot_linear_backward(cfg, gy.cuda(), w.cuda(), act, hot.HOT_Q_PER_TOKEN, gx, gw2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gw, gw2)
