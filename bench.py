@@ -23,10 +23,10 @@ INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA
 BF16_PEAK_TOPS = 2500.0     # MI355X dense bf16 MFMA (gw_bits = 16 variant)
 
 
-def stage_model(L, O, I, n, r, gx_bits, per_token, gw_bits=8):
+def stage_model(L, O, I, n, r, gx_bits, per_token, gw_bits=8, Lr=None):
     """Algorithmic work per launch of every kernel role: HBM bytes for the
     transform/quantise kernels, integer ops (and compulsory bytes) for the GEMMs."""
-    Lr = L // n * r
+    Lr = L // n * r if Lr is None else Lr
     cb = gx_bits / 8.0
     wb = gw_bits / 8.0
     m = {
@@ -182,6 +182,9 @@ def main() -> int:
                          "int8 matrix loop, and print them as JSON")
     ap.add_argument("--gw-bits", type=int, default=8, choices=[8, 16],
                     help="g_w operands: 8 = INT8 (the paper), 16 = bfloat16 variant")
+    ap.add_argument("--sample-tokens", type=int, default=0,
+                    help="tile the token axis per sample of this many tokens (197 for the ViT "
+                         "workloads) instead of as one run")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the timed step, run every layer of the workload once (compress "
                          "all, then backward all; chained where the workload is a chain) and print "
@@ -212,7 +215,7 @@ def main() -> int:
     L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep
     quant = args.quantizer or ("token" if wl.quantizer in ("token", "select") else "tensor")
     per_token = quant == "token"
-    cfg = hot.Config(block=n, keep=r, gw_bits=args.gw_bits)
+    cfg = hot.Config(block=n, keep=r, gw_bits=args.gw_bits, sample_tokens=args.sample_tokens)
 
     x, w, gy = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
     ws = hot.alloc_workspace(cfg, L, O, I)
@@ -253,7 +256,7 @@ def main() -> int:
     torch.cuda.synchronize()
     prof = hot.hot_debug_profile_end()
 
-    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token, cfg.gw_bits)
+    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token, cfg.gw_bits, cfg.reduced_tokens(L))
     kernels = {}
     for name, (ms, cnt) in prof.items():
         avg_us = ms * 1e3 / cnt
@@ -277,9 +280,9 @@ def main() -> int:
                     frac=round(d["TOPS"] / peak, 4), traffic=None,
                     algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
 
-    if quant == "token" and not args.one_call and args.gw_bits == 8:   # what the counter runs measured
+    if quant == "token" and not args.one_call and args.gw_bits == 8 and not args.sample_tokens:   # what the counter runs measured
         roof["traffic"] = profiled_traffic(wl.name, dominant)
-    Lr = L // n * r
+    Lr = cfg.reduced_tokens(L)
     ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
     value = ops_step / (ms_per_step * 1e-3) / 1e12
 
@@ -289,18 +292,24 @@ def main() -> int:
         Ls = L if args.cpu_sample_tokens <= 0 else min(L, max(n, args.cpu_sample_tokens // n * n))
         xs, gys, wh = x[:Ls].cpu().numpy(), gy[:Ls].cpu().numpy(), w.cpu().numpy()
         oracle.lib()
+        if cfg.sample_tokens:     # the oracle's per-sample definition: zero tokens after every sample
+            Ls = L
+            xs, gys = x.cpu().numpy(), gy.cpu().numpy()
+            xs_t, gys_t = oracle.pad_samples(xs, cfg.sample_tokens, n), oracle.pad_samples(gys, cfg.sample_tokens, n)
+        else:
+            xs_t, gys_t = xs, gys
         reps, dt = 0, 0.0
         while reps < 1 or (dt < args.cpu_seconds and reps < 64):
             t0 = time.perf_counter()
             oracle.backward_gx(gys, wh, n, bits=cfg.gx_bits, per_token=per_token, taps=False)
             if cfg.gw_bits == 16:
-                oracle.backward_gw_bf16(gys, oracle.compress_activation_bf16(xs, n, r), n, r)
+                oracle.backward_gw_bf16(gys_t, oracle.compress_activation_bf16(xs_t, n, r), n, r)
             else:
-                codes, sx = oracle.compress_activation(xs, n, r)
-                oracle.backward_gw(gys, codes, sx, n, r, taps=False)
+                codes, sx = oracle.compress_activation(xs_t, n, r)
+                oracle.backward_gw(gys_t, codes, sx, n, r, taps=False)
             dt += time.perf_counter() - t0
             reps += 1
-        ops_s = 2 * Ls * O * I + 2 * O * I * (Ls // n * r)
+        ops_s = 2 * Ls * O * I + 2 * O * I * cfg.reduced_tokens(Ls)
         cpu = dict(value=round(ops_s * reps / dt / 1e12, 6), unit="TOPS", cores=oracle.threads(), kind="oracle",
                    sample=f"{'all' if Ls == L else 'first ' + str(Ls) + ' of'} {L} tokens of {wl.name} "
                           f"(compress + g_x + g_w), {reps} passes in {dt:.1f} s",
@@ -314,6 +323,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
                    "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
+                   "sample_tokens": cfg.sample_tokens,
                    "step": "compress_activation + linear_backward_gx + linear_backward_gw" if not args.one_call
                    else "compress_activation + linear_backward (g_x and g_w in one call)"},
         "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,

@@ -61,10 +61,16 @@ typedef struct {
   int32_t gw_bits;         /* 8 (Sec. 5.2) | 16: bfloat16 operands, fp32 accumulation   */
   int32_t rounding;        /* hot_rounding                                            */
   float lqs_threshold;     /* 0.5 (Sec. 5.2.2)                                        */
+  int32_t sample_tokens;   /* 0: the L tokens are one run, tiled in blocks of n (needs
+                              L % n == 0).  S > 0: L = B x S tokens of B samples; the
+                              token-direction transform (ABC, g_w path) tiles every sample
+                              separately and pads its last block with zero tokens, so
+                              S need not be a multiple of n (ViT: S = 197); then
+                              L*r/n below reads B * ceil(S/n) * r                       */
 } hot_config;
 
 /* Fills *cfg with the paper's defaults: n = 16, r = 8, low-sequency rows, INT4 /
- * INT8, pseudo-stochastic rounding, threshold 0.5. */
+ * INT8, pseudo-stochastic rounding, threshold 0.5, one run of tokens. */
 void hot_default_config(hot_config* cfg);
 
 const char* hot_status_string(hot_status s);

@@ -254,3 +254,20 @@ def backward_gw_bf16(g_y, x_bits, n: int, r: int, keep=None):
     A = bf16_value(gh_bits).astype(np.float64)
     B = bf16_value(x_bits).astype(np.float64)
     return dict(g_w=(A.T @ B) / float(n), gh_bits=gh_bits)
+
+
+# ---- per-sample tiling of the token axis (the paper's ViT sequences have 197 tokens, not a
+# multiple of the block size, and it does not say how they are tiled) ---------------------
+
+def pad_samples(a, sample_tokens: int, n: int) -> np.ndarray:
+    """[B*S, C] -> [B*S', C] with S' = S rounded up to a multiple of n: every sample of S
+    tokens is followed by S' - S zero tokens, so that consecutive blocks of n never straddle
+    two samples.  Every token-direction function above applied to the padded tensors is the
+    per-sample definition (zero tokens add nothing to g_w)."""
+    a = _f32(a)
+    S = int(sample_tokens)
+    assert S > 0 and a.shape[0] % S == 0
+    B, Sp = a.shape[0] // S, -(-S // n) * n
+    out = np.zeros((B, Sp, a.shape[1]), dtype=np.float32)
+    out[:, :S, :] = a.reshape(B, S, a.shape[1])
+    return out.reshape(B * Sp, a.shape[1])

@@ -37,7 +37,7 @@ HOT_NUM_STAGES = 15
 class hot_config(C.Structure):
     _fields_ = [("block", C.c_int32), ("keep", C.c_int32), ("keep_idx", C.POINTER(C.c_int32)),
                 ("gx_bits", C.c_int32), ("gw_bits", C.c_int32), ("rounding", C.c_int32),
-                ("lqs_threshold", C.c_float)]
+                ("lqs_threshold", C.c_float), ("sample_tokens", C.c_int32)]
 
 
 class HotError(RuntimeError):
@@ -110,12 +110,20 @@ class Config:
     gw_bits: int = 8
     rounding: int = HOT_ROUND_PSEUDO_STOCHASTIC
     lqs_threshold: float = 0.5
+    sample_tokens: int = 0
+
+    def reduced_tokens(self, L: int) -> int:
+        """L' = tokens after HLA: L*r/n, or B * ceil(S/n) * r with per-sample tiling."""
+        if self.sample_tokens:
+            return L // self.sample_tokens * (-(-self.sample_tokens // self.block)) * self.keep
+        return L // self.block * self.keep
 
     def c(self) -> hot_config:
         cfg = hot_config()
         cfg.block, cfg.keep = int(self.block), int(self.keep)
         cfg.gx_bits, cfg.gw_bits = int(self.gx_bits), int(self.gw_bits)
         cfg.rounding, cfg.lqs_threshold = int(self.rounding), float(self.lqs_threshold)
+        cfg.sample_tokens = int(self.sample_tokens)
         if self.keep_idx is None:
             cfg.keep_idx = None
             self._keep_arr = None
@@ -271,7 +279,7 @@ def hot_select_quantizer(cfg: Config, g_y: torch.Tensor, ws: torch.Tensor,
 def hot_debug_unpack_activation(cfg: Config, act_buf: torch.Tensor, L: int, I: int, stream=None):
     """Returns (codes int8 [L*r/n, I], scale float32 [1]) on the device; with gw_bits = 16
     the codes are bfloat16 bit patterns (int16) and the scale is 1."""
-    Lr = L // cfg.block * cfg.keep
+    Lr = cfg.reduced_tokens(L)
     codes = torch.empty((Lr, I), dtype=torch.int16 if cfg.gw_bits == 16 else torch.int8,
                         device=act_buf.device)
     scale = torch.empty(1, dtype=torch.float32, device=act_buf.device)
@@ -302,7 +310,7 @@ def hot_debug_gw_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tensor, 
     """Returns dict(qg [L*r/n,O] int8, sg [1], acc [O,I] int32); with gw_bits = 16 qg holds
     bfloat16 bit patterns (int16) and acc the fp32 accumulators (float32)."""
     dev = ws.device
-    Lr = L // cfg.block * cfg.keep
+    Lr = cfg.reduced_tokens(L)
     qg = torch.empty((Lr, O), dtype=torch.int16 if cfg.gw_bits == 16 else torch.int8, device=dev)
     sg = torch.empty(1, dtype=torch.float32, device=dev)
     acc = torch.empty((O, I), dtype=torch.int32, device=dev) if want_acc else None
@@ -318,7 +326,7 @@ def hot_debug_fused_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tenso
                              I: int, gy_quantizer: int, want_acc: bool = True, stream=None):
     """Operands of the last hot_linear_backward: dict(qg, sg, qw, sw, acc_gx, qgh, sgh, acc_gw)."""
     dev = ws.device
-    Lr = L // cfg.block * cfg.keep
+    Lr = cfg.reduced_tokens(L)
     qg = torch.empty((L, O), dtype=torch.int8, device=dev)
     sg = torch.empty(L if gy_quantizer == HOT_Q_PER_TOKEN else 1, dtype=torch.float32, device=dev)
     qw = torch.empty((O, I), dtype=torch.int8, device=dev)

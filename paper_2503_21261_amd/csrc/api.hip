@@ -34,12 +34,14 @@ hot_status resolve_config(const hot_config* cfg, Config* out) {
   if (cfg->rounding != HOT_ROUND_NEAREST_EVEN && cfg->rounding != HOT_ROUND_PSEUDO_STOCHASTIC)
     return HOT_ERR_ARG;
   if (!(cfg->lqs_threshold >= 0.0f)) return HOT_ERR_ARG;
+  if (cfg->sample_tokens < 0) return HOT_ERR_ARG;
   out->n = n;
   out->r = r;
   out->gx_bits = cfg->gx_bits;
   out->gw_bits = cfg->gw_bits;
   out->rounding = cfg->rounding;
   out->lqs_threshold = cfg->lqs_threshold;
+  out->sample_tokens = cfg->sample_tokens;
   out->lowpass_default = cfg->keep_idx == nullptr;
   for (int k = 0; k < 64; ++k) out->map.pos[k] = -1;
   for (int j = 0; j < r; ++j) {
@@ -58,6 +60,17 @@ hot_status resolve_config(const hot_config* cfg, Config* out) {
   return HOT_OK;
 }
 
+RowTiling row_tiling(const Config& c, int64_t L) {
+  RowTiling t{0, c.sample_tokens, 1};
+  if (c.sample_tokens == 0) {
+    if (L >= c.n && L % c.n == 0) t.nblk = L / c.n;
+  } else if (L >= c.sample_tokens && L % c.sample_tokens == 0) {
+    t.bps = (int)ceil_div(c.sample_tokens, c.n);
+    t.nblk = L / c.sample_tokens * t.bps;
+  }
+  return t;
+}
+
 GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GxLayout g;
   g.pitch = round_up(O * c.gx_bits / 8, kPitchAlign);
@@ -71,7 +84,7 @@ GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
 
 GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GwLayout g;
-  g.Lr = L / c.n * c.r;
+  g.Lr = row_tiling(c, L).nblk * c.r;
   g.pitch = round_up(g.Lr * (c.gw_bits / 8), kPitchAlign);
   g.plan = plan_gemm(O, I, g.pitch, c.gw_bits, c.gw_bits == 8);
   g.scalars = 0;
@@ -112,7 +125,7 @@ WeightLayout weight_layout(const Config& c, int64_t O, int64_t I) {
 
 ActLayout act_layout(const Config& c, int64_t L, int64_t I) {
   ActLayout a;
-  a.Lr = L / c.n * c.r;
+  a.Lr = row_tiling(c, L).nblk * c.r;
   a.pitch = round_up(a.Lr * (c.gw_bits / 8), kPitchAlign);
   a.codes = kHeaderBytes;
   a.total = a.codes + (size_t)(I * a.pitch);
@@ -127,8 +140,9 @@ bool gx_shape_ok(const Config& c, int64_t L, int64_t O, int64_t I) {
 }
 bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
   // the int32 bound on L' only binds integer accumulators; bfloat16 operands sum in fp32
-  return cols >= 1 && L >= c.n && L % c.n == 0 && cols < (1ll << 31) && L < (1ll << 31) &&
-         (c.gw_bits == 16 || L / c.n * c.r <= kMaxK8);
+  const int64_t nblk = row_tiling(c, L).nblk;
+  return cols >= 1 && nblk >= 1 && cols < (1ll << 31) && L < (1ll << 31) &&
+         (c.gw_bits == 16 || nblk * c.r <= kMaxK8);
 }
 
 KeepMap identity_map(int n) {
@@ -166,6 +180,7 @@ void hot_default_config(hot_config* cfg) {
   cfg->gw_bits = 8;
   cfg->rounding = HOT_ROUND_PSEUDO_STOCHASTIC;
   cfg->lqs_threshold = 0.5f;
+  cfg->sample_tokens = 0;
 }
 
 const char* hot_status_string(hot_status s) {
@@ -220,10 +235,10 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   uint8_t* base = (uint8_t*)act_buf;
   float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
   if (c.gw_bits == 16) {
-    HOT_TRY(launch_col_bf16(x, L, I, c, base + a.codes, a.pitch, (float*)base, s, kStActQuant));
+    HOT_TRY(launch_col_bf16(x, row_tiling(c, L), I, c, base + a.codes, a.pitch, (float*)base, s, kStActQuant));
     return HOT_OK;
   }
-  HOT_TRY(launch_col_quant(x, L, I, c, c.r, c.map, false, c.gw_bits, base + a.codes, a.pitch,
+  HOT_TRY(launch_col_quant(x, row_tiling(c, L), I, c, c.r, c.map, false, c.gw_bits, base + a.codes, a.pitch,
                            (float*)base, partials, s, kStActAbsmax, kStActQuant));
   return HOT_OK;
 }
@@ -246,7 +261,7 @@ hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O,
   const WeightLayout wl = weight_layout(c, O, I);
   uint8_t* base = (uint8_t*)wq_buf;
   float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, base + wl.codes,
+  HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, base + wl.codes,
                            wl.pitch, (float*)base, partials, s, kStWAbsmax, kStWQuant));
   return HOT_OK;
 }
@@ -294,7 +309,7 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   float* part_w = (float*)(base + kHeaderBytes);
   uint8_t* qw = base + g.qw;
   // H.w along O, one scale, written as [I x O] code rows
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
+  HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
                            part_w, s, kStWAbsmax, kStWQuant));
   return run_gx(c, g_y, qw, s_w, L, O, I, gy_quantizer, g_x, base, g, s);
 }
@@ -342,9 +357,9 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
 
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
   if (c.gw_bits == 16)
-    HOT_TRY(launch_col_bf16(g_y, L, O, c, qg, g.pitch, s_g, s, kStGyTQuant));
+    HOT_TRY(launch_col_bf16(g_y, row_tiling(c, L), O, c, qg, g.pitch, s_g, s, kStGyTQuant));
   else
-    HOT_TRY(launch_col_quant(g_y, L, O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
+    HOT_TRY(launch_col_quant(g_y, row_tiling(c, L), O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
                              kStGyTAbsmax, kStGyTQuant));
   HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.plan, partial,
                        nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
@@ -363,7 +378,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c) || c.gw_bits == 16) {
+  if (!gy_fused_supported(c) || c.gw_bits == 16 || c.sample_tokens != 0) {
     st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
     if (st != HOT_OK) return st;
     return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
@@ -385,7 +400,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
   const uint8_t* abase = (const uint8_t*)act_buf;
   const bool per_token = gy_quantizer == HOT_Q_PER_TOKEN;
 
-  HOT_TRY(launch_col_quant(w, O, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, f.gx.pitch, s_w,
+  HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, f.gx.pitch, s_w,
                            part_a, s, kStWAbsmax, kStWQuant));
   HOT_TRY(launch_gy_fused(g_y, L, O, c, per_token, qg, f.gx.pitch, s_g, qgh, f.gw.pitch, s_gh, part_a,
                           part_b, (float*)(base + f.rowpart), s, kStGyFusedAbsmax, kStGyFusedQuant));
@@ -522,7 +537,7 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const
   if (st != HOT_OK) return st;
   if (!ws || (acc_gw && !act_buf)) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c) || c.gw_bits == 16) return HOT_ERR_UNIMPLEMENTED;
+  if (!gy_fused_supported(c) || c.gw_bits == 16 || c.sample_tokens != 0) return HOT_ERR_UNIMPLEMENTED;
   st = hot_debug_gx_operands(cfg, ws, L, O, I, gy_quantizer, gy_codes, gy_scales, w_codes, w_scale,
                              acc_gx, stream);
   if (st != HOT_OK) return st;

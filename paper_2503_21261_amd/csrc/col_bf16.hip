@@ -13,7 +13,7 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 }
 
 template <int N, int KIND>
-__global__ __launch_bounds__(256) void col_bf16_kernel(const float* __restrict__ x, int64_t R,
+__global__ __launch_bounds__(256) void col_bf16_kernel(const float* __restrict__ x, RowTiling rt,
                                                        int64_t C, KeepMap map, int r, int kbw,
                                                        uint8_t* __restrict__ out, int64_t pitch,
                                                        float* __restrict__ scale) {
@@ -23,7 +23,7 @@ __global__ __launch_bounds__(256) void col_bf16_kernel(const float* __restrict__
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int bpb = 2 * (KIND == kKeepLowHalf ? N / 2 : r);   // bytes per block and column
   const int TB = 4 * kbw * bpb, TBP = TB + 4;
-  const int64_t nblk = R / N;
+  const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
   const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
   const int64_t c0 = tx * CT + lane;
@@ -38,7 +38,10 @@ __global__ __launch_bounds__(256) void col_bf16_kernel(const float* __restrict__
     const int64_t gb = ty * 4 * kbw + slot;
     if (gb >= nblk || !col_ok) continue;
     float v[1][kept_vals<N, KIND>()];
-    load_block_kept<N, 1, KIND>(x + gb * N * C + c0, C, v);
+    int64_t first;
+    int valid;
+    block_rows<N>(rt, gb, first, valid);
+    load_block_kept<N, 1, KIND>(x + first * C + c0, C, valid, v);
     uint8_t* dst = tile + lane * TBP + slot * bpb;
     if constexpr (KIND == kKeepLowHalf) {
 #pragma unroll
@@ -61,32 +64,32 @@ __global__ __launch_bounds__(256) void col_bf16_kernel(const float* __restrict__
 
 namespace {
 template <int N>
-hipError_t launch_n(const float* x, int64_t R, int64_t C, const Config& cfg, uint8_t* out,
+hipError_t launch_n(const float* x, const RowTiling& rt, int64_t C, const Config& cfg, uint8_t* out,
                     int64_t pitch, float* scale, hipStream_t s) {
   const bool low = cfg.lowpass_default && cfg.r * 2 == cfg.n;
   const int bpb = 2 * cfg.r;
-  const int64_t nblk = R / N;
+  const int64_t nblk = rt.nblk;
   int kbw = 128 / bpb;
   kbw = kbw < 1 ? 1 : (kbw > 8 ? 8 : kbw);
   auto tiles = [&](int k) { return ceil_div(C, 64) * ceil_div(nblk, 4 * k); };
   while (tiles(kbw) < 512 && kbw > 1) kbw /= 2;
   const size_t lds = (size_t)64 * (4 * kbw * bpb + 4);
   const dim3 grid((unsigned)tiles(kbw));
-  if (low) col_bf16_kernel<N, kKeepLowHalf><<<grid, dim3(256), lds, s>>>(x, R, C, cfg.map, cfg.r, kbw, out, pitch, scale);
-  else col_bf16_kernel<N, kKeepGeneric><<<grid, dim3(256), lds, s>>>(x, R, C, cfg.map, cfg.r, kbw, out, pitch, scale);
+  if (low) col_bf16_kernel<N, kKeepLowHalf><<<grid, dim3(256), lds, s>>>(x, rt, C, cfg.map, cfg.r, kbw, out, pitch, scale);
+  else col_bf16_kernel<N, kKeepGeneric><<<grid, dim3(256), lds, s>>>(x, rt, C, cfg.map, cfg.r, kbw, out, pitch, scale);
   return hipGetLastError();
 }
 }  // namespace
 
-hipError_t launch_col_bf16(const float* x, int64_t R, int64_t C, const Config& cfg, uint8_t* out,
+hipError_t launch_col_bf16(const float* x, const RowTiling& rt, int64_t C, const Config& cfg, uint8_t* out,
                            int64_t pitch, float* scale, hipStream_t s, int stage) {
-  if (R <= 0 || C <= 0) return hipSuccess;
+  if (rt.nblk <= 0 || C <= 0) return hipSuccess;
   hipError_t e = hipErrorInvalidValue;
   stage_begin(stage, s);
   switch (cfg.n) {
-    case 16: e = launch_n<16>(x, R, C, cfg, out, pitch, scale, s); break;
-    case 32: e = launch_n<32>(x, R, C, cfg, out, pitch, scale, s); break;
-    case 64: e = launch_n<64>(x, R, C, cfg, out, pitch, scale, s); break;
+    case 16: e = launch_n<16>(x, rt, C, cfg, out, pitch, scale, s); break;
+    case 32: e = launch_n<32>(x, rt, C, cfg, out, pitch, scale, s); break;
+    case 64: e = launch_n<64>(x, rt, C, cfg, out, pitch, scale, s); break;
   }
   stage_end(stage, s);
   return e;

@@ -22,14 +22,13 @@ uint32_t next_tag() {
 
 void set_exchange_wait_us(int us) { g_exchange_wait_us.store(us); }
 
-ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity) {
+ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity) {
   ColPlan p;
   if (bits == 4) p.kind = kKeepAll4;
   else if (identity && r == n) p.kind = kKeepAll8;
   else if (lowpass_default && r * 2 == n) p.kind = kKeepLowHalf;
   else p.kind = kKeepGeneric;
   const int bpb = bits == 4 ? n / 2 : r;
-  const int64_t nblk = R / n;
   const int vmax = n == 64 ? 2 : 4;  // at most 128 block values per lane stay in registers
   const int vdiv = (C % 4 == 0) ? 4 : (C % 2 == 0 ? 2 : 1);
   auto tiles = [&](int vec, int kbw) { return ceil_div(C, 64 * vec) * ceil_div(nblk, 4 * kbw); };
@@ -56,7 +55,8 @@ namespace {
 
 struct ColArgs {
   const float* x;
-  int64_t R, C;
+  RowTiling rows;
+  int64_t C;
   KeepMap map;
   int r, rounding;
   uint8_t* codes;
@@ -68,14 +68,14 @@ struct ColArgs {
 template <int N, int VEC, int KIND>
 hipError_t launch_absmax(const ColArgs& a, const ColPlan& p, hipStream_t s) {
   col_absmax_kernel<N, VEC, KIND><<<dim3((unsigned)p.absmax_grid), dim3(256), 0, s>>>(
-      a.x, a.R, a.C, a.map, p.kbw_a, a.partials);
+      a.x, a.rows, a.C, a.map, p.kbw_a, a.partials);
   return hipGetLastError();
 }
 
 template <int N, int VEC, int KIND>
 hipError_t launch_quant(const ColArgs& a, const ColPlan& p, hipStream_t s) {
   col_quant_kernel<N, VEC, KIND><<<dim3((unsigned)p.tiles_q), dim3(256), p.lds_q, s>>>(
-      a.x, a.R, a.C, a.map, a.r, a.rounding, p.kbw_q, a.partials, p.absmax_grid, a.codes, a.pitch,
+      a.x, a.rows, a.C, a.map, a.r, a.rounding, p.kbw_q, a.partials, p.absmax_grid, a.codes, a.pitch,
       a.scale);
   return hipGetLastError();
 }
@@ -90,7 +90,7 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
   } else {
     if (*done || a.C % VEC != 0) return hipSuccess;
     const int bpb = KIND == kKeepGeneric ? a.r : (KIND == kKeepAll8 ? N : N / 2);
-    const int64_t tiles = ceil_div(a.C, 64 * VEC) * ceil_div(a.R / N, 4 * KB);
+    const int64_t tiles = ceil_div(a.C, 64 * VEC) * ceil_div(a.rows.nblk, 4 * KB);
     size_t lds = (size_t)(64 * VEC) * (4 * KB * bpb + 4);
     if (lds < onepass_stage_bytes<N, VEC, KIND>()) lds = onepass_stage_bytes<N, VEC, KIND>();
     auto kern = col_quant_onepass_kernel<N, VEC, KIND, KB>;
@@ -114,7 +114,7 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
     const int wait_us = g_exchange_wait_us.load();
     stage_begin(sq, s);
     kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(
-        a.x, a.R, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
+        a.x, a.rows, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
         next_tag(), (long long)wait_us * 100, a.codes, a.pitch, a.scale);
     stage_end(sq, s);
     *done = true;
@@ -168,14 +168,14 @@ hipError_t launch_n(const ColArgs& a, const ColPlan& p, hipStream_t s, int sa, i
 
 }  // namespace
 
-hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& cfg, int r,
+hipError_t launch_col_quant(const float* x, const RowTiling& rows, int64_t C, const Config& cfg, int r,
                             const KeepMap& map, bool identity, int bits, uint8_t* codes,
                             int64_t pitch, float* scale, float* partials, hipStream_t s,
                             int stage_absmax, int stage_quant) {
-  if (R <= 0 || C <= 0) return hipSuccess;
+  if (rows.nblk <= 0 || C <= 0) return hipSuccess;
   if (bits == 4 && !(identity && r == cfg.n)) return hipErrorInvalidValue;
-  const ColPlan p = plan_col(R, C, cfg.n, r, bits, cfg.lowpass_default && !identity, identity);
-  const ColArgs a{x, R, C, map, r, cfg.rounding, codes, pitch, scale, partials};
+  const ColPlan p = plan_col(rows.nblk, C, cfg.n, r, bits, cfg.lowpass_default && !identity, identity);
+  const ColArgs a{x, rows, C, map, r, cfg.rounding, codes, pitch, scale, partials};
   switch (cfg.n) {
     case 16: return launch_n<16>(a, p, s, stage_absmax, stage_quant);
     case 32: return launch_n<32>(a, p, s, stage_absmax, stage_quant);

@@ -43,6 +43,21 @@ __host__ __device__ constexpr int lowpass_row(int n, int j) {
   return r;
 }
 
+// First row of block gb and how many of its N rows are real tokens (the rest are zeros).
+template <int N>
+__device__ __forceinline__ void block_rows(const RowTiling& t, int64_t gb, int64_t& first, int& valid) {
+  if (t.S == 0) {
+    first = gb * N;
+    valid = N;
+  } else {
+    const int64_t b = gb / t.bps;
+    const int64_t j = gb - b * t.bps;
+    first = b * t.S + j * N;
+    const int64_t left = t.S - j * N;
+    valid = left < N ? (int)left : N;
+  }
+}
+
 // Which kept-row list the kernel was compiled for.
 enum KeepKind {
   kKeepGeneric = 0,   // any list, from the KeepMap argument; INT8 codes, one LDS byte each
@@ -52,13 +67,33 @@ enum KeepKind {
 };
 
 // Load one block (N rows x VEC columns per lane) and transform it in registers.
+// N rows starting at `src` (row stride C floats), `col` floats into each row.  Rows
+// k >= valid are the zero padding of a sample's last block: they re-read the last real row
+// (never past it) and are zeroed.  The full block keeps compile-time row offsets; the
+// padded one steps a pointer, so neither pays a 64-bit multiply per row.
+template <int N, class VT>
+__device__ __forceinline__ void load_n_rows(const float* __restrict__ src, int64_t C, uint32_t col,
+                                            int valid, VT (&q)[N]) {
+  if (valid >= N) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) q[k] = *reinterpret_cast<const VT*>(src + (int64_t)k * C + col);
+  } else {
+    const float* p = src;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      q[k] = *reinterpret_cast<const VT*>(p + col);
+      if (k >= valid) q[k] = VT{};
+      if (k + 1 < valid) p += C;
+    }
+  }
+}
+
 template <int N, int VEC>
-__device__ __forceinline__ void load_block_fwht(const float* __restrict__ src, int64_t C,
+__device__ __forceinline__ void load_block_fwht(const float* __restrict__ src, int64_t C, int valid,
                                                 float (&v)[VEC][N]) {
   using VT = typename VecT<VEC>::type;
   VT q[N];
-#pragma unroll
-  for (int k = 0; k < N; ++k) q[k] = *reinterpret_cast<const VT*>(src + (int64_t)k * C);
+  load_n_rows<N, VT>(src, C, 0u, valid, q);
 #pragma unroll
   for (int k = 0; k < N; ++k) {
     float o[VEC];
@@ -175,11 +210,14 @@ constexpr int kept_vals() { return KIND == kKeepLowHalf ? N / 2 : N; }
 // the lane's 32-bit column offset, so the row stride is added on the scalar unit.
 template <int N, int VEC>
 __device__ __forceinline__ void load_rows(const float* __restrict__ rows, int64_t C, uint32_t col,
-                                          bool ok, typename VecT<VEC>::type (&q)[N]) {
+                                          bool ok, int valid, typename VecT<VEC>::type (&q)[N]) {
   using VT = typename VecT<VEC>::type;
+  if (ok) {
+    load_n_rows<N, VT>(rows, C, col, valid, q);
+  } else {
 #pragma unroll
-  for (int k = 0; k < N; ++k)
-    q[k] = ok ? *reinterpret_cast<const VT*>(rows + (int64_t)k * C + col) : VT{};
+    for (int k = 0; k < N; ++k) q[k] = VT{};
+  }
 }
 
 // Transform loaded rows into kept form (see load_block_kept).
@@ -213,14 +251,13 @@ __device__ __forceinline__ void transform_kept(const typename VecT<VEC>::type (&
 // Load one block and return its transformed values in kept form: all N natural rows, or
 // (kKeepLowHalf) the even natural rows, row 2j' at index j'.
 template <int N, int VEC, int KIND>
-__device__ __forceinline__ void load_block_kept(const float* __restrict__ src, int64_t C,
+__device__ __forceinline__ void load_block_kept(const float* __restrict__ src, int64_t C, int valid,
                                                 float (&v)[VEC][kept_vals<N, KIND>()]) {
   if constexpr (KIND == kKeepLowHalf) {
     float full[VEC][N];
     using VT = typename VecT<VEC>::type;
     VT q[N];
-#pragma unroll
-    for (int k = 0; k < N; ++k) q[k] = *reinterpret_cast<const VT*>(src + (int64_t)k * C);
+    load_n_rows<N, VT>(src, C, 0u, valid, q);
 #pragma unroll
     for (int k = 0; k < N; ++k) {
       float o[VEC];
@@ -231,7 +268,7 @@ __device__ __forceinline__ void load_block_kept(const float* __restrict__ src, i
 #pragma unroll
     for (int vi = 0; vi < VEC; ++vi) fwht_even_rows<N>(full[vi], v[vi]);
   } else {
-    load_block_fwht<N, VEC>(src, C, v);
+    load_block_fwht<N, VEC>(src, C, valid, v);
   }
 }
 
@@ -289,13 +326,13 @@ __device__ __forceinline__ float workgroup_max(float m) {
 // Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
 // grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
 template <int N, int VEC, int KIND>
-__global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, int64_t R,
+__global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, RowTiling rt,
                                                          int64_t C, KeepMap map, int kbw,
                                                          float* __restrict__ partials) {
   constexpr int CT = 64 * VEC;
   __shared__ float s_max[4];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
-  const int64_t nblk = R / N;
+  const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
   const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
   float m = 0.0f;
@@ -307,7 +344,10 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict
       const int64_t gb = ty * 4 * kbw + w * kbw + kb;
       if (gb >= nblk) break;
       float v[VEC][kept_vals<N, KIND>()];
-      load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v);
+      int64_t first;
+      int valid;
+      block_rows<N>(rt, gb, first, valid);
+      load_block_kept<N, VEC, KIND>(x + first * C + c0, C, valid, v);
       m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v, map));
     }
   }
@@ -322,7 +362,7 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict
 // writes and the row-wise read-out).
 template <int N, int VEC, int KIND>
 __global__ __launch_bounds__(256) void col_quant_kernel(
-    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding, int kbw,
+    const float* __restrict__ x, RowTiling rt, int64_t C, KeepMap map, int r, int rounding, int kbw,
     const float* __restrict__ partials, int npartials, uint8_t* __restrict__ codes, int64_t pitch,
     float* __restrict__ scale) {
   constexpr int CT = 64 * VEC;
@@ -333,7 +373,7 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
   const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
   const int TB = 4 * kbw * bpb;      // code bytes per column in this tile
   const int TBP = TB + 4;            // odd number of dwords
-  const int64_t nblk = R / N;
+  const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
   const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
   const int64_t c0 = tx * CT + lane * VEC;
@@ -353,7 +393,10 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
     const int64_t gb = ty * 4 * kbw + slot;
     if (gb >= nblk || !col_ok) continue;
     float v[VEC][kept_vals<N, KIND>()];
-    load_block_kept<N, VEC, KIND>(x + gb * N * C + c0, C, v);
+    int64_t first;
+    int valid;
+    block_rows<N>(rt, gb, first, valid);
+    load_block_kept<N, VEC, KIND>(x + first * C + c0, C, valid, v);
     store_kept_form_codes<N, VEC, KIND>(v, tile, lane, slot * bpb, TBP, map, inv, rounding);
   }
   __syncthreads();
@@ -422,7 +465,7 @@ constexpr size_t onepass_stage_bytes() { return (size_t)kept_vals<N, KIND>() * 2
 template <int N, int VEC, int KIND, int KB>
 __global__ __launch_bounds__(256, 2)
 void col_quant_onepass_kernel(
-    const float* __restrict__ x, int64_t R, int64_t C, KeepMap map, int r, int rounding,
+    const float* __restrict__ x, RowTiling rt, int64_t C, KeepMap map, int r, int rounding,
     unsigned long long* __restrict__ slots, uint32_t tag, long long wait_ticks,
     uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scale) {
   constexpr int CT = 64 * VEC;
@@ -434,7 +477,7 @@ void col_quant_onepass_kernel(
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
   const int TB = 4 * KB * bpb, TBP = TB + 4;
-  const int64_t nblk = R / N;
+  const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
   const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
   const int64_t c0 = tx * CT + lane * VEC;
@@ -450,18 +493,21 @@ void col_quant_onepass_kernel(
   const int64_t gb0 = ty * 4 * KB + __builtin_amdgcn_readfirstlane(w) * KB;
   const float* tile_x = x + tx * CT;
   uint32_t col = (uint32_t)lane * VEC;
-  if constexpr (DEPTH == 2)
-    load_rows<N, VEC>(tile_x + gb0 * N * C, C, col, gb0 < nblk && col_ok, q[0]);
+  // rows of block gb (clamped to a real block when gb is past the end: nothing is loaded then)
+  auto issue = [&](int64_t gb, VT(&dst)[N]) {
+    int64_t first;
+    int valid;
+    block_rows<N>(rt, gb < nblk ? gb : nblk - 1, first, valid);
+    load_rows<N, VEC>(tile_x + first * C, C, col, gb < nblk && col_ok, valid, dst);
+  };
+  if constexpr (DEPTH == 2) issue(gb0, q[0]);
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
     VT(&cur)[N] = q[kb % DEPTH];
     if constexpr (DEPTH == 2) {
-      if (kb + 1 < KB) {
-        const int64_t gn = gb0 + kb + 1;
-        load_rows<N, VEC>(tile_x + gn * N * C, C, col, gn < nblk && col_ok, q[(kb + 1) % 2]);
-      }
+      if (kb + 1 < KB) issue(gb0 + kb + 1, q[(kb + 1) % 2]);
     } else {
-      load_rows<N, VEC>(tile_x + (gb0 + kb) * N * C, C, col, gb0 + kb < nblk && col_ok, cur);
+      issue(gb0 + kb, cur);
     }
     transform_kept<N, VEC, KIND>(cur, v[kb]);   // zeros for a block past the end
     m = fmaxf(m, kept_form_absmax<N, VEC, KIND>(v[kb], map));
@@ -526,18 +572,29 @@ void col_quant_onepass_kernel(
       for (int kb = 0; kb < KB; ++kb) {
         const int64_t gb = bty * 4 * KB + w * KB + kb;
         if (gb >= nblk) break;
-        const float* src = x + gb * N * C + bc0;
+        int64_t first;
+        int valid;
+        block_rows<N>(rt, gb, first, valid);
+        const float* src = x + first * C + bc0;
+        auto row = [&](int k, float (&o)[VEC]) {   // zero padding past the sample's last token
+          if (k < valid) {
+            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)k * C), o);
+          } else {
+#pragma unroll
+            for (int vi = 0; vi < VEC; ++vi) o[vi] = 0.0f;
+          }
+        };
 #pragma unroll 1
         for (int j = 0; j < NS; ++j) {
           float a[VEC];
           if constexpr (KIND == kKeepLowHalf) {
             float lo[VEC], hi[VEC];
-            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)(2 * j) * C), lo);
-            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)(2 * j + 1) * C), hi);
+            row(2 * j, lo);
+            row(2 * j + 1, hi);
 #pragma unroll
             for (int vi = 0; vi < VEC; ++vi) a[vi] = lo[vi] + hi[vi];
           } else {
-            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)j * C), a);
+            row(j, a);
           }
 #pragma unroll
           for (int vi = 0; vi < VEC; ++vi) stage[j * 256 * VEC + vi] = a[vi];
@@ -634,6 +691,6 @@ struct ColPlan {
   size_t lds_q;
 };
 
-ColPlan plan_col(int64_t R, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity);
+ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity);
 
 }  // namespace hot

@@ -17,9 +17,19 @@ struct KeepMap {
   int8_t pos[64];
 };
 
+// How the token rows of a tensor are cut into blocks of n for the token-direction
+// transform: one contiguous run (S = 0), or samples of S tokens each tiled separately, the
+// last block of a sample padded with zero tokens (bps blocks per sample).
+struct RowTiling {
+  int64_t nblk;   // blocks in the whole tensor
+  int64_t S;
+  int bps;
+};
+
 // Validated, resolved form of hot_config.
 struct Config {
   int n, r, gx_bits, gw_bits, rounding;
+  int64_t sample_tokens;   // 0 = the whole token axis is one run
   float lqs_threshold;
   int keep[64];   // r natural-order indices, in output order
   KeepMap map;    // inverse of keep
@@ -27,6 +37,8 @@ struct Config {
 };
 
 hot_status resolve_config(const hot_config* cfg, Config* out);
+// Blocks of the token axis of an L-token tensor (nblk = 0 when L does not fit the tiling).
+RowTiling row_tiling(const Config& c, int64_t L);
 
 // K-contiguous operand rows are padded with zero codes to a multiple of 128 bytes.
 constexpr int64_t kPitchAlign = 128;
@@ -110,13 +122,13 @@ hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, i
                             int rounding, int mode, uint8_t* codes, int64_t pitch, float* scales,
                             float* partials, int* npartials, hipStream_t s);
 
-// Column-direction block WHT (blocks of n consecutive rows of x [R x C]), keep r
+// Column-direction block WHT (blocks of n rows of x [. x C], cut as `rows` says), keep r
 // rows per block, one scale for the tensor; output transposed: row c of `codes`
 // holds the kept values of column c, reduced row index contiguous.  Runs the
 // abs-max pass (partials, kMaxPartials floats of scratch) and the quantise pass;
 // *scale is written, pad bytes up to `pitch` are zero-filled.  `identity` says the
 // kept list is 0..n-1 (required for bits == 4).
-hipError_t launch_col_quant(const float* x, int64_t R, int64_t C, const Config& cfg, int r,
+hipError_t launch_col_quant(const float* x, const RowTiling& rows, int64_t C, const Config& cfg, int r,
                             const KeepMap& map, bool identity, int bits, uint8_t* codes,
                             int64_t pitch, float* scale, float* partials, hipStream_t s,
                             int stage_absmax, int stage_quant);
@@ -134,7 +146,7 @@ hipError_t launch_gy_fused(const float* g_y, int64_t L, int64_t O, const Config&
 
 // bfloat16 form of the same transposed low-rank operand (g_w path with gw_bits = 16):
 // out row c holds the kept values of column c as bfloat16; *scale is set to 1.
-hipError_t launch_col_bf16(const float* x, int64_t R, int64_t C, const Config& cfg, uint8_t* out,
+hipError_t launch_col_bf16(const float* x, const RowTiling& rows, int64_t C, const Config& cfg, uint8_t* out,
                            int64_t pitch, float* scale, hipStream_t s, int stage);
 
 // Bounded wait of the single-pass column kernel (microseconds; < 0: always two passes).

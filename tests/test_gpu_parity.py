@@ -65,9 +65,12 @@ def check_gw(hot, cfg, gy, x, what):
     I = x.shape[1]
     _say(f"[gw] {what} L={L} O={O} I={I} n={cfg.block} r={cfg.keep} keep={cfg.keep_idx} round={cfg.rounding}")
     keep = None if cfg.keep_idx is None else list(cfg.keep_idx)
-    codes_ref, sx_ref = oracle.compress_activation(x.numpy(), cfg.block, cfg.keep, keep=keep,
+    S = cfg.sample_tokens
+    xo = oracle.pad_samples(x.numpy(), S, cfg.block) if S else x.numpy()
+    gyo = oracle.pad_samples(gy.numpy(), S, cfg.block) if S else gy.numpy()
+    codes_ref, sx_ref = oracle.compress_activation(xo, cfg.block, cfg.keep, keep=keep,
                                                    rounding=cfg.rounding)
-    ref = oracle.backward_gw(gy.numpy(), codes_ref, sx_ref, cfg.block, cfg.keep, keep=keep,
+    ref = oracle.backward_gw(gyo, codes_ref, sx_ref, cfg.block, cfg.keep, keep=keep,
                              rounding=cfg.rounding)
     assert ref["overflow"] == 0
     gyd, xd = gy.cuda(), x.cuda()
@@ -630,8 +633,11 @@ def check_gw_bf16(hot, cfg, gy, x, what):
     n, r = cfg.block, cfg.keep
     _say(f"[gw bf16] {what} L={L} O={O} I={I} n={n} r={r} keep={cfg.keep_idx}")
     keep = None if cfg.keep_idx is None else list(cfg.keep_idx)
-    xb_ref = oracle.compress_activation_bf16(x.numpy(), n, r, keep)
-    ref = oracle.backward_gw_bf16(gy.numpy(), xb_ref, n, r, keep)
+    S = cfg.sample_tokens
+    xo = oracle.pad_samples(x.numpy(), S, n) if S else x.numpy()
+    gyo = oracle.pad_samples(gy.numpy(), S, n) if S else gy.numpy()
+    xb_ref = oracle.compress_activation_bf16(xo, n, r, keep)
+    ref = oracle.backward_gw_bf16(gyo, xb_ref, n, r, keep)
     gyd, xd = gy.cuda(), x.cuda()
     act = hot.alloc_act_buffer(cfg, L, I)
     ws = hot.alloc_workspace(cfg, L, O, I)
@@ -647,7 +653,7 @@ def check_gw_bf16(hot, cfg, gy, x, what):
     assert sx.item() == 1.0 and taps["sg"].item() == 1.0
     assert_close_maxnorm(taps["acc"].cpu().numpy(), ref["g_w"] * n, what + " accumulators")
     assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w")
-    Lr = L // n * r
+    Lr = cfg.reduced_tokens(L)
     assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((2 * Lr + 127) // 128 * 128)
     return ref, gw
 
@@ -681,3 +687,44 @@ def test_gw_bf16_config2_full_size():
     hot.hot_linear_backward(cfg, gy.cuda(), w.cuda(), act, hot.HOT_Q_PER_TOKEN, gx, gw2, ws)
     torch.cuda.synchronize()
     assert torch.equal(gw, gw2)
+
+
+# ---- per-sample tiling of the token axis (sample_tokens > 0) ---------------------------------
+
+RAGGED_CASES = [
+    # B, S, O, I, n, r, keep_idx
+    (4, 197, 130, 72, 16, 8, None),       # ViT sequence: 12 blocks + one of 5 tokens
+    (3, 197, 96, 40, 32, 16, None),
+    (2, 197, 64, 24, 64, 32, None),
+    (5, 10, 48, 16, 16, 8, None),         # samples shorter than a block
+    (6, 64, 40, 24, 16, 8, None),         # multiple of the block: same result as one run
+    (4, 50, 33, 20, 16, 3, None),         # generic kept list
+    (16, 197, 200, 136, 16, 8, None),     # several row tiles
+]
+
+
+@pytest.mark.parametrize("case", RAGGED_CASES)
+@pytest.mark.parametrize("wait_us", [-1, 0, 200])
+def test_gw_per_sample_tiling(exchange_wait, case, wait_us):
+    B, S, O, I, n, r, keep_idx = case
+    hot = _hot()
+    exchange_wait(wait_us)
+    x, w, gy = make(B * S, O, I, seed=61)
+    cfg = hot.Config(block=n, keep=r, keep_idx=keep_idx, sample_tokens=S)
+    ref, gw = check_gw(hot, cfg, gy, x, f"per-sample S={S} wait={wait_us}")
+    if S % n == 0:
+        flat = hot.Config(block=n, keep=r, keep_idx=keep_idx)
+        _, gw_flat = check_gw(hot, flat, gy, x, "same tokens as one run")
+        assert torch.equal(gw, gw_flat)
+    if wait_us == 200:
+        check_gw_bf16(hot, hot.Config(block=n, keep=r, keep_idx=keep_idx, gw_bits=16, sample_tokens=S),
+                      gy, x, f"per-sample bf16 S={S}")
+
+
+def test_per_sample_tiling_shape_errors_and_gx_is_unaffected():
+    hot = _hot()
+    cfg = hot.Config(block=16, keep=8, sample_tokens=197)
+    assert hot.hot_act_buffer_bytes(cfg, 4 * 197, 64) == 256 + 64 * ((4 * 13 * 8 + 127) // 128 * 128)
+    assert hot.hot_act_buffer_bytes(cfg, 4 * 197 + 1, 64) == 0      # not a whole number of samples
+    x, w, gy = make(2 * 197, 64, 24, seed=62)
+    check_gx(hot, cfg, gy, w, True, "g_x with sample_tokens set")     # L need not be a multiple of n

@@ -386,3 +386,24 @@ def test_bf16_gw_full_rank_reproduces_the_exact_gradient_for_bf16_exact_inputs()
     xb = oracle.compress_activation_bf16(x, n, n, keep)
     out = oracle.backward_gw_bf16(gy, xb, n, n, keep)
     assert np.array_equal(out["g_w"], gy.astype(np.float64).T @ x.astype(np.float64))
+
+
+# ---- per-sample tiling -------------------------------------------------------------------
+
+def test_per_sample_tiling_is_the_concatenation_of_independent_samples_and_exact_at_full_rank():
+    rng = np.random.default_rng(21)
+    B, S, O, I, n, r = 3, 23, 6, 5, 16, 8        # 23 tokens: one full block and one of 7 + 9 zeros
+    gy = rng.integers(-4, 5, size=(B * S, O)).astype(np.float32)
+    x = rng.integers(-4, 5, size=(B * S, I)).astype(np.float32)
+    keep = oracle.lowpass_index(n, r)
+    whole = oracle.hla(oracle.pad_samples(x, S, n), n, r, keep)
+    Sp = 32
+    for b in range(B):      # each sample on its own, padded by hand
+        one = np.zeros((Sp, I), dtype=np.float32)
+        one[:S] = x[b * S:(b + 1) * S]
+        assert np.array_equal(whole[b * (Sp // n) * r:(b + 1) * (Sp // n) * r], oracle.hla(one, n, r, keep))
+    # full rank: the zero tokens contribute nothing, the product is the exact gradient
+    full = np.arange(n, dtype=np.int32)
+    gh = oracle.hla(oracle.pad_samples(gy, S, n), n, n, full).astype(np.float64)
+    xh = oracle.hla(oracle.pad_samples(x, S, n), n, n, full).astype(np.float64)
+    assert np.array_equal(gh.T @ xh / n, gy.astype(np.float64).T @ x.astype(np.float64))
