@@ -10,10 +10,12 @@
 // Four waves take different blocks; their codes are gathered in LDS as
 // [column][reduced-row bytes] and written out as contiguous runs per column, so
 // the matrix-core GEMM that follows reads both operands K-contiguous and nothing
-// is ever transposed in a separate pass.  HBM-bound: the tensor-wide scale forces
-// two reads of the input (abs-max pass, quantise pass).  The abs-max pass leaves
-// one partial maximum per workgroup; the quantise pass reduces them itself, so no
-// atomics and no zero-initialised memory are needed.
+// is ever transposed in a separate pass.  HBM-bound.  The tensor-wide scale is a true
+// dependency on every element: tensors whose kept values fit the register files of the
+// resident workgroups are read once (col_quant_onepass_kernel: the maxima are exchanged
+// through memory while the values wait in registers); larger ones are read twice (abs-max
+// pass leaving one partial maximum per workgroup, quantise pass reducing them itself).
+// Neither form needs atomics on data or zero-initialised memory.
 #pragma once
 #include <type_traits>
 

@@ -98,7 +98,7 @@ WeightLayout weight_layout(const Config& c, int64_t O, int64_t I);
 
 // Kernel roles for the optional stage timer (names in profile.hip).
 enum Stage {
-  kStFill = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
+  kStUnused = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
   kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStGwReduce, kStGyFusedAbsmax,
   kStGyFusedQuant
 };
@@ -124,8 +124,9 @@ hipError_t launch_row_quant(const float* t, int64_t rows, int64_t cols, int n, i
 
 // Column-direction block WHT (blocks of n rows of x [. x C], cut as `rows` says), keep r
 // rows per block, one scale for the tensor; output transposed: row c of `codes`
-// holds the kept values of column c, reduced row index contiguous.  Runs the
-// abs-max pass (partials, kMaxPartials floats of scratch) and the quantise pass;
+// holds the kept values of column c, reduced row index contiguous.  Runs the single-pass
+// kernel when the tensor fits it (timed as stage_quant), else the abs-max pass and the
+// quantise pass; `partials` is kMaxPartials floats of scratch either way;
 // *scale is written, pad bytes up to `pitch` are zero-filled.  `identity` says the
 // kept list is 0..n-1 (required for bits == 4).
 hipError_t launch_col_quant(const float* x, const RowTiling& rows, int64_t C, const Config& cfg, int r,
