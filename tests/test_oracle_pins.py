@@ -407,3 +407,33 @@ def test_per_sample_tiling_is_the_concatenation_of_independent_samples_and_exact
     gh = oracle.hla(oracle.pad_samples(gy, S, n), n, n, full).astype(np.float64)
     xh = oracle.hla(oracle.pad_samples(x, S, n), n, n, full).astype(np.float64)
     assert np.array_equal(gh.T @ xh / n, gy.astype(np.float64).T @ x.astype(np.float64))
+
+
+# ---- values the paper itself prints (fixtures under tests/golden/, each with its citation) ----
+
+def _golden(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    return np.array(rows, dtype=np.float64)
+
+
+def test_golden_h2_sign_matrix_and_its_transform():
+    S = _golden("hadamard_h2.txt")
+    assert np.array_equal(oracle.hadamard(4).astype(np.float64), S)
+    v = np.array([3.0, -1.0, 4.0, 1.5], dtype=np.float32)
+    assert np.array_equal(oracle.fwht(v).astype(np.float64), S @ v.astype(np.float64))
+    # one more application of the recurrence, H_3 = H_1 (x) H_2, checked block by block
+    H8 = oracle.hadamard(8).astype(np.float64)
+    assert np.array_equal(H8[:4, :4], S) and np.array_equal(H8[:4, 4:], S)
+    assert np.array_equal(H8[4:, :4], S) and np.array_equal(H8[4:, 4:], -S)
+
+
+def test_golden_activation_buffer_ratio():
+    frac, stored, orig, ratio = _golden("abc_ratio.txt")[0]
+    assert frac * stored / orig == ratio
+    L, I, n = 512, 96, 16
+    r = int(n * frac)
+    x = np.random.default_rng(3).standard_normal((L, I)).astype(np.float32)
+    codes, _ = oracle.compress_activation(x, n, r)
+    assert codes.dtype == np.int8 and codes.nbytes == ratio * x.nbytes
