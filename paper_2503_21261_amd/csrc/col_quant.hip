@@ -2,6 +2,7 @@
 // (col_quant_kernel.h).
 #include <atomic>
 #include <chrono>
+#include <mutex>
 
 #include "col_quant_kernel.h"
 
@@ -97,8 +98,10 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
     constexpr size_t lds_tile_max = (size_t)(64 * VEC) * (4 * KB * N + 4);   // bpb <= N
     constexpr size_t lds_max = lds_tile_max > onepass_stage_bytes<N, VEC, KIND>()
                                    ? lds_tile_max : onepass_stage_bytes<N, VEC, KIND>();
-    static int per_cu = -1, cus = 0;   // per instantiation, for the LDS size last asked for
+    static std::mutex mu;              // per instantiation: the cached occupancy below
+    static int per_cu = -1, cus = 0;   // for the LDS size last asked for
     static size_t lds_seen = 0;
+    std::lock_guard<std::mutex> lock(mu);
     if (per_cu < 0 || lds != lds_seen) {
       int dev = 0, nb = 0;
       hipError_t e = hipGetDevice(&dev);
@@ -111,11 +114,16 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
       lds_seen = lds;
     }
     if (tiles > (int64_t)per_cu * cus || tiles > kMaxPartials / 2) return hipSuccess;
-    const int wait_us = g_exchange_wait_us.load();
+    // the other workgroups need at least the time to stream their share of the input:
+    // never wait less than the whole tensor takes at 1 TB/s (0 stays 0: tests force the
+    // self-computed path with it)
+    int64_t wait_us = g_exchange_wait_us.load();
+    const int64_t stream_us = a.rows.nblk * N * a.C * 4 / 1000000;
+    if (wait_us > 0 && wait_us < stream_us) wait_us = stream_us;
     stage_begin(sq, s);
     kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(
         a.x, a.rows, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
-        next_tag(), (long long)wait_us * 100, a.codes, a.pitch, a.scale);
+        next_tag(), (long long)(wait_us * 100), a.codes, a.pitch, a.scale);
     stage_end(sq, s);
     *done = true;
     return hipGetLastError();

@@ -1,5 +1,7 @@
 // Launchers of the integer GEMM (kernel in igemm_kernel.h), the split-K reduction and
 // the code unpacker used by the parity views.
+#include <atomic>
+
 #include "hot_host.h"
 #include "igemm_kernel.h"
 
@@ -97,11 +99,11 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, hipStream_t s, int gemm_stag
   g.tiles_n = (int)ceil_div(g.N, BN);
   const size_t lds = 2 * (size_t)(BM + BN) * BKB;
   auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4, BF16>;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};  // per instantiation; setting it twice is harmless
+  if (!attr_set.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   const dim3 grid((unsigned)((int64_t)g.tiles_m * g.tiles_n), 1, (unsigned)g.split);
   if (gemm_stage >= 0) stage_begin(gemm_stage, s);
