@@ -108,23 +108,20 @@ def run_sweep(torch, hot, hot_inputs, wl, quantizer_flag):
         q = hot.HOT_Q_PER_TOKEN if quant == "token" else hot.HOT_Q_PER_TENSOR
         g_x = torch.empty((l.L, l.I), device="cuda")
         g_w = torch.empty((l.O, l.I), device="cuda")
-        e0, e1, e2 = ev(), ev(), ev()
+        e0, e1 = ev(), ev()
         e0.record()
-        hot.hot_linear_backward_gx(cfg, g_y, w, q, g_x, ws)
+        hot.hot_linear_backward(cfg, g_y, w, acts[k], q, g_x, g_w, ws)
         e1.record()
-        hot.hot_linear_backward_gw(cfg, g_y, acts[k], l.I, g_w, ws)
-        e2.record()
         torch.cuda.synchronize()
-        gx_us, gw_us = e0.elapsed_time(e1) * 1e3, e1.elapsed_time(e2) * 1e3
-        Lr = l.L // n * r
-        row.update(gy_quantizer=quant, gx_us=round(gx_us, 1), gw_us=round(gw_us, 1),
-                   gx_TOPS=round(2.0 * l.L * l.O * l.I / gx_us / 1e6, 1),
-                   gw_TOPS=round(2.0 * l.O * l.I * Lr / gw_us / 1e6, 1),
+        bw_us = e0.elapsed_time(e1) * 1e3
+        Lr = cfg.reduced_tokens(l.L)
+        row.update(gy_quantizer=quant, backward_us=round(bw_us, 1),
+                   backward_TOPS=round((2.0 * l.L * l.O * l.I + 2.0 * l.O * l.I * Lr) / bw_us / 1e6, 1),
                    finite=bool(torch.isfinite(g_x).all().item() and torch.isfinite(g_w).all().item()))
         acts[k] = None
         g_y = g_x if chain else None
         del w, g_w
-    total_us = sum(x["compress_us"] + x["gx_us"] + x["gw_us"] for x in rows)
+    total_us = sum(x["compress_us"] + x["backward_us"] for x in rows)
     ops = sum(2.0 * l.L * l.O * l.I + 2.0 * l.O * l.I * (l.L // n * r) for _, l in layers)
     return dict(workload=wl.name, layers=rows, total_us=round(total_us, 1),
                 effective_TOPS=round(ops / total_us / 1e6, 1),
@@ -173,10 +170,10 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="repeat the oracle on the sample until about this much CPU wall time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--one-call", action="store_true",
-                    help="run the backward as hot_linear_backward (two shared passes over g_y, "
-                         "vector-ALU-bound) instead of hot_linear_backward_gx + "
-                         "hot_linear_backward_gw (three HBM-bound passes, faster on MI355X)")
+    ap.add_argument("--backward", default="auto", choices=["auto", "separate", "shared"],
+                    help="how hot_linear_backward produces the two views of g_y: the library's "
+                         "choice (default), always the two separate paths, or the shared g_y "
+                         "passes wherever they exist")
     ap.add_argument("--probe-peaks", action="store_true",
                     help="instead of the workload, time plain HBM read/write and a register-only "
                          "int8 matrix loop, and print them as JSON")
@@ -208,6 +205,7 @@ def main() -> int:
         return 0
     wl = hot_inputs.WORKLOADS[args.workload]
     if args.sweep:
+        hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2}[args.backward])
         run_sweep(torch, hot, hot_inputs, wl, args.quantizer)   # warm-up: code objects, allocator
         print(json.dumps(run_sweep(torch, hot, hot_inputs, wl, args.quantizer)))
         return 0
@@ -224,14 +222,11 @@ def main() -> int:
     gw = torch.empty((O, I), device="cuda")
     q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
     stream = torch.cuda.current_stream()
+    hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2}[args.backward])
 
     def step():
         hot.hot_compress_activation(cfg, x, act, ws, stream=stream)
-        if not args.one_call:
-            hot.hot_linear_backward_gx(cfg, gy, w, q, gx, ws, stream=stream)
-            hot.hot_linear_backward_gw(cfg, gy, act, I, gw, ws, stream=stream)
-        else:
-            hot.hot_linear_backward(cfg, gy, w, act, q, gx, gw, ws, stream=stream)
+        hot.hot_linear_backward(cfg, gy, w, act, q, gx, gw, ws, stream=stream)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(gy)
@@ -280,7 +275,7 @@ def main() -> int:
                     frac=round(d["TOPS"] / peak, 4), traffic=None,
                     algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
 
-    if quant == "token" and not args.one_call and args.gw_bits == 8 and not args.sample_tokens:   # what the counter runs measured
+    if quant == "token" and args.backward == "auto" and args.gw_bits == 8 and not args.sample_tokens:   # what the counter runs measured
         roof["traffic"] = profiled_traffic(wl.name, dominant)
     Lr = cfg.reduced_tokens(L)
     ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
@@ -324,8 +319,7 @@ def main() -> int:
         "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
                    "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
                    "sample_tokens": cfg.sample_tokens,
-                   "step": "compress_activation + linear_backward_gx + linear_backward_gw" if not args.one_call
-                   else "compress_activation + linear_backward (g_x and g_w in one call)"},
+                   "step": "compress_activation + linear_backward (g_x and g_w; g_y views: %s)" % args.backward},
         "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
     }

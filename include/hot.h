@@ -141,11 +141,12 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
 /*
  * Both gradients of one layer in one call (Sec. 5.1 and 5.2 on the same g_y): the same
  * g_x and g_w, bit for bit, as hot_linear_backward_gx followed by
- * hot_linear_backward_gw, but the two quantised views of g_y (rotated along O, and
- * HLA-compressed along L) come out of shared reads of g_y: two passes over it instead
- * of three (four with a per-tensor g_y scale).  Block sizes 16 and 32 take the shared
- * passes; block size 64 runs the two separate paths one after the other.
- * Arguments as for the two separate calls.  Requires O % n == 0 and L % n == 0.
+ * hot_linear_backward_gw.  Where it is faster (16-row blocks and a g_y too large for the
+ * single-pass token-direction kernel) the two quantised views of g_y (rotated along O,
+ * and HLA-compressed along L) come out of shared reads of g_y: two passes over it instead
+ * of three; otherwise the two separate paths run one after the other.
+ * Arguments as for the two separate calls.  Requires O % n == 0 and L % n == 0
+ * (or whole samples with sample_tokens).
  */
 hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const float* w,
                                const void* act_buf, int64_t L, int64_t O, int64_t I,
@@ -202,6 +203,11 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const
                                     int8_t* gy_codes, float* gy_scales, int8_t* w_codes,
                                     float* w_scale, int32_t* acc_gx, int8_t* gyT_codes,
                                     float* gyT_scale, int32_t* acc_gw, void* stream);
+
+/* Strategy of hot_linear_backward: 0 = chosen by the library (default), 1 = always the two
+ * separate paths, 2 = the shared passes over g_y whenever they exist (block sizes 16 and
+ * 32, INT8 g_w operands, one run of tokens).  Results do not depend on it.  Process-wide. */
+hot_status hot_debug_set_backward_strategy(int strategy);
 
 /* Tensors small enough to stay in the register files of the resident workgroups (x and
  * w of the ViT-sized layers) are transformed and quantised by a single-pass kernel whose

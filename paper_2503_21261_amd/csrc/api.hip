@@ -3,6 +3,8 @@
 // allocated here; everything lives in caller-provided buffers.
 #include <string.h>
 
+#include <atomic>
+
 #include "hot_host.h"
 
 namespace hot {
@@ -145,6 +147,28 @@ bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
          (c.gw_bits == 16 || nblk * c.r <= kMaxK8);
 }
 
+// How hot_linear_backward produces the two views of g_y: 0 = by measurement (below),
+// 1 = always the two separate paths, 2 = the shared passes whenever they exist.
+std::atomic<int> g_backward_strategy{0};
+
+bool shared_gy_passes_exist(const Config& c) {
+  return gy_fused_supported(c) && c.gw_bits == 8 && c.sample_tokens == 0;
+}
+
+// The shared passes read g_y twice but are bound by the vector ALUs; the separate paths read
+// it two or three times at HBM speed.  Measured on MI355X: the shared passes win for
+// 16-row blocks once the HLA view no longer fits the single-pass kernel (its kept values,
+// 4 bytes each, beyond about 80 MB of registers: three HBM passes otherwise); they lose for
+// 32-row blocks (one more butterfly stage across lanes) and whenever the single pass applies.
+bool shared_gy_passes(const Config& c, int64_t L, int64_t O) {
+  if (!shared_gy_passes_exist(c)) return false;
+  const int strategy = g_backward_strategy.load();
+  if (strategy == 1) return false;
+  if (strategy == 2) return true;
+  const int64_t kept_bytes = row_tiling(c, L).nblk * c.r * O * 4;
+  return c.n == 16 && kept_bytes > 80ll * 1000 * 1000;
+}
+
 KeepMap identity_map(int n) {
   KeepMap m;
   for (int k = 0; k < 64; ++k) m.pos[k] = k < n ? (int8_t)k : (int8_t)-1;
@@ -214,7 +238,7 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
   if (tok_shape_ok(c, L, O) && tok_shape_ok(c, L, I)) {
     const size_t a = gw_layout(c, L, O, I).total;
     need = a > need ? a : need;
-    if (gx_shape_ok(c, L, O, I) && gy_fused_supported(c)) {
+    if (gx_shape_ok(c, L, O, I) && shared_gy_passes_exist(c)) {
       const size_t b = fused_layout(c, L, O, I).total;
       need = b > need ? b : need;
     }
@@ -378,7 +402,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c) || c.gw_bits == 16 || c.sample_tokens != 0) {
+  if (!shared_gy_passes(c, L, O)) {
     st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
     if (st != HOT_OK) return st;
     return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
@@ -461,6 +485,12 @@ hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_bu
   return HOT_OK;
 }
 
+hot_status hot_debug_set_backward_strategy(int strategy) {
+  if (strategy < 0 || strategy > 2) return HOT_ERR_ARG;
+  g_backward_strategy.store(strategy);
+  return HOT_OK;
+}
+
 hot_status hot_debug_set_exchange_wait_us(int us) {
   set_exchange_wait_us(us);
   return HOT_OK;
@@ -537,7 +567,7 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const
   if (st != HOT_OK) return st;
   if (!ws || (acc_gw && !act_buf)) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
-  if (!gy_fused_supported(c) || c.gw_bits == 16 || c.sample_tokens != 0) return HOT_ERR_UNIMPLEMENTED;
+  if (!shared_gy_passes(c, L, O)) return HOT_ERR_UNIMPLEMENTED;
   st = hot_debug_gx_operands(cfg, ws, L, O, I, gy_quantizer, gy_codes, gy_scales, w_codes, w_scale,
                              acc_gx, stream);
   if (st != HOT_OK) return st;

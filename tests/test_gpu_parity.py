@@ -438,9 +438,14 @@ def check_fused(hot, cfg, gy, x, w, per_token, what):
     gx = torch.empty((L, I), dtype=torch.float32, device="cuda")
     gw = torch.empty((O, I), dtype=torch.float32, device="cuda")
     q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
-    hot.hot_linear_backward(cfg, gyd, wd, act, q, gx, gw, ws)
+    hot.hot_debug_set_backward_strategy(2)      # the shared passes wherever they exist
+    try:
+        hot.hot_linear_backward(cfg, gyd, wd, act, q, gx, gw, ws)
+        if cfg.block != 64:
+            t = hot.hot_debug_fused_operands(cfg, ws, act, L, O, I, q)
+    finally:
+        hot.hot_debug_set_backward_strategy(0)
     if cfg.block != 64:
-        t = hot.hot_debug_fused_operands(cfg, ws, act, L, O, I, q)
         torch.cuda.synchronize()
         assert bits_equal(t["sg"].cpu().numpy(), ref_x["sg"]), f"{what}: g_y scales differ"
         assert bits_equal(t["sw"].cpu().numpy(), ref_x["sw"]), f"{what}: w scale differs"
@@ -459,6 +464,11 @@ def check_fused(hot, cfg, gy, x, w, per_token, what):
     hot.hot_linear_backward_gw(cfg, gyd, act, I, gw2, ws)
     torch.cuda.synchronize()
     assert torch.equal(gx, gx2) and torch.equal(gw, gw2), f"{what}: differs from the separate calls"
+    # the library's own choice of strategy gives the same bits again
+    gx3, gw3 = torch.empty_like(gx), torch.empty_like(gw)
+    hot.hot_linear_backward(cfg, gyd, wd, act, q, gx3, gw3, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gx, gx3) and torch.equal(gw, gw3), f"{what}: differs under the default strategy"
 
 
 FUSED_CASES = [
