@@ -174,6 +174,9 @@ def main() -> int:
                     help="how hot_linear_backward produces the two views of g_y: the library's "
                          "choice (default), always the two separate paths, or the shared g_y "
                          "passes wherever they exist")
+    ap.add_argument("--gemm", type=int, default=0,
+                    help="work distribution of the GEMMs: 0 = the library's choice (default), 1 = one "
+                         "workgroup per output tile, s >= 2 = s K slices wherever a split applies")
     ap.add_argument("--probe-peaks", action="store_true",
                     help="instead of the workload, time plain HBM read/write and a register-only "
                          "int8 matrix loop, and print them as JSON")
@@ -204,6 +207,7 @@ def main() -> int:
         print(json.dumps(probe_peaks(torch, hot)))
         return 0
     wl = hot_inputs.WORKLOADS[args.workload]
+    hot.hot_debug_set_gemm_mode(args.gemm)
     if args.sweep:
         hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2}[args.backward])
         run_sweep(torch, hot, hot_inputs, wl, args.quantizer)   # warm-up: code objects, allocator
@@ -319,7 +323,8 @@ def main() -> int:
         "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
                    "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
                    "sample_tokens": cfg.sample_tokens,
-                   "step": "compress_activation + linear_backward (g_x and g_w; g_y views: %s)" % args.backward},
+                   "step": "compress_activation + linear_backward (g_x and g_w; g_y views: %s; GEMM work "
+                           "distribution: %s)" % (args.backward, {0: "auto", 1: "tile"}.get(args.gemm, "K split %d" % args.gemm))},
         "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,
         "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
     }

@@ -180,9 +180,9 @@ hot_status hot_debug_unpack_weight(const hot_config* cfg, const void* wq_buf, in
 /* Operands left in `ws` by the last hot_linear_backward_gx with these arguments:
  * codes of the rotated g_y [L x O] and w [O x I] (row-major, one code per byte),
  * scales of g_y ([L] per token, [1] per tensor) and of w [1], and the int32
- * integer product [L x I] recomputed from those operands.  Any output may be
- * NULL. */
-hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t L, int64_t O,
+ * integer product [L x I] recomputed from those operands by the GEMM the call itself
+ * used (the GEMM scratch at the end of `ws` is overwritten).  Any output may be NULL. */
+hot_status hot_debug_gx_operands(const hot_config* cfg, void* ws, int64_t L, int64_t O,
                                  int64_t I, hot_quantizer gy_quantizer, int8_t* gy_codes,
                                  float* gy_scales, int8_t* w_codes, float* w_scale, int32_t* acc,
                                  void* stream);
@@ -192,13 +192,13 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t 
  * from those codes and act_buf.  Any output may be NULL.  With gw_bits = 16 the codes are
  * bfloat16 bit patterns (two bytes each) and `acc` receives the fp32 accumulators' bit
  * patterns. */
-hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+hot_status hot_debug_gw_operands(const hot_config* cfg, void* ws, const void* act_buf,
                                  int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
                                  float* gy_scale, int32_t* acc, void* stream);
 
 /* Operands left in `ws` by the last hot_linear_backward (block size 16 or 32): the
  * outputs of both views above.  Any output may be NULL. */
-hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+hot_status hot_debug_fused_operands(const hot_config* cfg, void* ws, const void* act_buf,
                                     int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
                                     int8_t* gy_codes, float* gy_scales, int8_t* w_codes,
                                     float* w_scale, int32_t* acc_gx, int8_t* gyT_codes,
@@ -214,8 +214,16 @@ hot_status hot_debug_set_backward_strategy(int strategy);
  * workgroups exchange their abs-max through the workspace and wait for each other at most
  * `us` microseconds (default 200) before computing what is missing themselves; results
  * do not depend on the value.  us = 0: never wait (exercises the self-computed path);
- * us < 0: always use the two-pass kernels.  Process-wide setting. */
+ * us < 0: always use the two-pass kernels.  The same bound (us <= 0: never wait) applies
+ * to a split-K GEMM's wait for another workgroup's partial sums.  Process-wide setting. */
 hot_status hot_debug_set_exchange_wait_us(int us);
+
+/* Work distribution of the GEMMs: 0 = chosen by the library (default), 1 = one workgroup
+ * per output tile, s = 2..8: the K range cut into s slices, one workgroup each, wherever a
+ * split applies (integer operands, small tile, at least 4 K stages per slice); the slices'
+ * partial sums are handed to the last one through the workspace.  Integer results, and
+ * therefore all outputs, do not depend on it.  Process-wide. */
+hot_status hot_debug_set_gemm_mode(int mode);
 
 /* ---- stage timing for benchmarks (off by default) ---- */
 

@@ -29,7 +29,7 @@ EXPORTS = (
     "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
     "hot_linear_backward", "hot_select_quantizer", "hot_debug_unpack_activation",
     "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us",
-    "hot_debug_set_backward_strategy", "hot_debug_profile_begin", "hot_debug_profile_end",
+    "hot_debug_set_backward_strategy", "hot_debug_set_gemm_mode", "hot_debug_profile_begin", "hot_debug_profile_end",
     "hot_debug_stage_name", "hot_debug_probe",
 )
 HOT_NUM_STAGES = 15
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
         l.hot_debug_fused_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int] + [vp] * 9
         l.hot_debug_set_exchange_wait_us.argtypes = [C.c_int]
         l.hot_debug_set_backward_strategy.argtypes = [C.c_int]
+        l.hot_debug_set_gemm_mode.argtypes = [C.c_int]
         l.hot_debug_profile_begin.argtypes = []
         l.hot_debug_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int64)]
         l.hot_debug_probe.argtypes = [C.c_int, vp, sz, C.c_int, vp]
@@ -348,6 +349,11 @@ def hot_debug_fused_operands(cfg: Config, ws: torch.Tensor, act_buf: torch.Tenso
 def hot_debug_set_backward_strategy(strategy: int) -> None:
     """0 = library's choice, 1 = separate paths, 2 = shared g_y passes where they exist."""
     _check(lib().hot_debug_set_backward_strategy(int(strategy)), "hot_debug_set_backward_strategy")
+
+
+def hot_debug_set_gemm_mode(mode: int) -> None:
+    """0: library's choice, 1: one workgroup per output tile, s >= 2: s K slices where a split applies."""
+    _check(lib().hot_debug_set_gemm_mode(int(mode)), "hot_debug_set_gemm_mode")
 
 
 def hot_debug_set_exchange_wait_us(us: int) -> None:

@@ -80,7 +80,8 @@ GxLayout gx_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   g.sg = kWsPrefix;
   g.qg = g.sg + (size_t)round_up(L * 4, 256);
   g.qw = g.qg + (size_t)(L * g.pitch);
-  g.total = g.qw + (size_t)(I * g.pitch);
+  g.partial = (size_t)round_up((int64_t)(g.qw + (size_t)(I * g.pitch)), 256);
+  g.total = g.partial + gemm_scratch_bytes(L, I, g.pitch, c.gx_bits);
   return g;
 }
 
@@ -88,11 +89,10 @@ GwLayout gw_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   GwLayout g;
   g.Lr = row_tiling(c, L).nblk * c.r;
   g.pitch = round_up(g.Lr * (c.gw_bits / 8), kPitchAlign);
-  g.plan = plan_gemm(O, I, g.pitch, c.gw_bits, c.gw_bits == 8);
   g.scalars = 0;
   g.qg = kWsPrefix;
   g.partial = g.qg + (size_t)round_up(O * g.pitch, 256);
-  g.total = g.partial + g.plan.partial_bytes;
+  g.total = g.partial + gemm_scratch_bytes(O, I, g.pitch, c.gw_bits);
   return g;
 }
 
@@ -112,8 +112,10 @@ FusedLayout fused_layout(const Config& c, int64_t L, int64_t O, int64_t I) {
   f.s_gh = 16;
   f.rowpart = (size_t)round_up((int64_t)f.gx.total, 256);
   f.qgh = f.rowpart + (size_t)round_up(gy_fused_tiles_x(O) * L * 4, 256);
-  f.partial = f.qgh + (size_t)round_up(O * f.gw.pitch, 256);
-  f.total = f.partial + f.gw.plan.partial_bytes;
+  f.partial = f.qgh + (size_t)round_up(O * f.gw.pitch, 256);   // shared by the two GEMMs
+  const size_t sx = gemm_scratch_bytes(L, I, f.gx.pitch, c.gx_bits);
+  const size_t sw = gemm_scratch_bytes(O, I, f.gw.pitch, c.gw_bits);
+  f.total = f.partial + (sx > sw ? sx : sw);
   return f;
 }
 
@@ -292,6 +294,17 @@ hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O,
 
 namespace {
 
+// One GEMM on K-contiguous operands of `pitch` bytes, planned for its shape, with the
+// scratch region at base + partial_off and the flag slots of the workspace prefix.
+hipError_t gemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t pitch, int bits,
+                uint8_t* base, size_t partial_off, int32_t* out_i32, float* out_f32,
+                const float* row_scale, int row_stride, const float* col_scale, int n, hipStream_t s,
+                int stage = -1) {
+  return launch_igemm(A, B, M, N, pitch, pitch, bits, plan_gemm(M, N, pitch, bits, true),
+                      (int32_t*)(base + partial_off), (unsigned long long*)(base + kGemmFlagsOffset),
+                      out_i32, out_f32, row_scale, row_stride, col_scale, n, s, stage);
+}
+
 // The g_x path given quantised weights (codes [I x pitch], scale): rotate and quantise
 // g_y, multiply, dequantise.
 hot_status run_gx(const Config& c, const float* g_y, const uint8_t* qw, const float* s_w, int64_t L,
@@ -307,9 +320,8 @@ hot_status run_gx(const Config& c, const float* g_y, const uint8_t* qw, const fl
     HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
     HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
   }
-  HOT_TRY(launch_igemm(qg, qw, L, I, g.pitch, g.pitch, c.gx_bits,
-                       plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
-                       gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
+  HOT_TRY(gemm(qg, qw, L, I, g.pitch, c.gx_bits, base, g.partial, nullptr, g_x, s_g,
+               gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
 
@@ -376,7 +388,6 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   float* s_g = (float*)(base + g.scalars);
   float* part_g = (float*)(base + kHeaderBytes);
   uint8_t* qg = base + g.qg;
-  int32_t* partial = g.plan.split > 1 ? (int32_t*)(base + g.partial) : nullptr;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
   // HLA(g_y) along L, one scale, written as [O x L'] code rows
@@ -385,8 +396,8 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   else
     HOT_TRY(launch_col_quant(g_y, row_tiling(c, L), O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
                              kStGyTAbsmax, kStGyTQuant));
-  HOT_TRY(launch_igemm(qg, abase + a.codes, O, I, g.pitch, g.pitch, c.gw_bits, g.plan, partial,
-                       nullptr, g_w, s_g, 0, (const float*)abase, c.n, s, kStGwGemm, kStGwReduce));
+  HOT_TRY(gemm(qg, abase + a.codes, O, I, g.pitch, c.gw_bits, base, g.partial, nullptr, g_w, s_g, 0,
+               (const float*)abase, c.n, s, kStGwGemm));
   return HOT_OK;
 }
 
@@ -420,7 +431,6 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
   uint8_t* qg = base + f.gx.qg;
   uint8_t* qw = base + f.gx.qw;
   uint8_t* qgh = base + f.qgh;
-  int32_t* partial = f.gw.plan.split > 1 ? (int32_t*)(base + f.partial) : nullptr;
   const uint8_t* abase = (const uint8_t*)act_buf;
   const bool per_token = gy_quantizer == HOT_Q_PER_TOKEN;
 
@@ -428,12 +438,10 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
                            part_a, s, kStWAbsmax, kStWQuant));
   HOT_TRY(launch_gy_fused(g_y, L, O, c, per_token, qg, f.gx.pitch, s_g, qgh, f.gw.pitch, s_gh, part_a,
                           part_b, (float*)(base + f.rowpart), s, kStGyFusedAbsmax, kStGyFusedQuant));
-  HOT_TRY(launch_igemm(qg, qw, L, I, f.gx.pitch, f.gx.pitch, c.gx_bits,
-                       plan_gemm(L, I, f.gx.pitch, c.gx_bits, false), nullptr, nullptr, g_x, s_g,
-                       per_token ? 1 : 0, s_w, c.n, s, kStGxGemm));
-  HOT_TRY(launch_igemm(qgh, abase + a.codes, O, I, f.gw.pitch, f.gw.pitch, c.gw_bits, f.gw.plan,
-                       partial, nullptr, g_w, s_gh, 0, (const float*)abase, c.n, s, kStGwGemm,
-                       kStGwReduce));
+  HOT_TRY(gemm(qg, qw, L, I, f.gx.pitch, c.gx_bits, base, f.partial, nullptr, g_x, s_g,
+               per_token ? 1 : 0, s_w, c.n, s, kStGxGemm));
+  HOT_TRY(gemm(qgh, abase + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial, nullptr, g_w, s_gh,
+               0, (const float*)abase, c.n, s, kStGwGemm));
   return HOT_OK;
 }
 
@@ -493,6 +501,13 @@ hot_status hot_debug_set_backward_strategy(int strategy) {
 
 hot_status hot_debug_set_exchange_wait_us(int us) {
   set_exchange_wait_us(us);
+  set_gemm_wait_us(us);
+  return HOT_OK;
+}
+
+hot_status hot_debug_set_gemm_mode(int mode) {
+  if (mode < 0 || mode > 8) return HOT_ERR_ARG;
+  set_gemm_mode(mode);
   return HOT_OK;
 }
 
@@ -511,7 +526,7 @@ hot_status hot_debug_unpack_weight(const hot_config* cfg, const void* wq_buf, in
   return HOT_OK;
 }
 
-hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t L, int64_t O,
+hot_status hot_debug_gx_operands(const hot_config* cfg, void* ws, int64_t L, int64_t O,
                                  int64_t I, hot_quantizer gy_quantizer, int8_t* gy_codes,
                                  float* gy_scales, int8_t* w_codes, float* w_scale, int32_t* acc,
                                  void* stream) {
@@ -522,7 +537,7 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t 
   if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
   const GxLayout g = gx_layout(c, L, O, I);
   hipStream_t s = (hipStream_t)stream;
-  const uint8_t* base = (const uint8_t*)ws;
+  uint8_t* base = (uint8_t*)ws;
   if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, L, O, g.pitch, c.gx_bits, 0, gy_codes, s));
   if (w_codes) HOT_TRY(launch_unpack(base + g.qw, I, O, g.pitch, c.gx_bits, 1, w_codes, s));
   if (gy_scales)
@@ -530,13 +545,12 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, const void* ws, int64_t 
                            hipMemcpyDeviceToDevice, s));
   if (w_scale) HOT_TRY(hipMemcpyAsync(w_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(launch_igemm(base + g.qg, base + g.qw, L, I, g.pitch, g.pitch, c.gx_bits,
-                         plan_gemm(L, I, g.pitch, c.gx_bits, false), nullptr, acc, nullptr, nullptr,
-                         0, nullptr, c.n, s));
+    HOT_TRY(gemm(base + g.qg, base + g.qw, L, I, g.pitch, c.gx_bits, base, g.partial, acc, nullptr,
+                 nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
 
-hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+hot_status hot_debug_gw_operands(const hot_config* cfg, void* ws, const void* act_buf,
                                  int64_t L, int64_t O, int64_t I, int8_t* gy_codes,
                                  float* gy_scale, int32_t* acc, void* stream) {
   Config c;
@@ -547,17 +561,16 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, const void* ws, const vo
   const GwLayout g = gw_layout(c, L, O, I);
   const ActLayout a = act_layout(c, L, I);
   hipStream_t s = (hipStream_t)stream;
-  const uint8_t* base = (const uint8_t*)ws;
+  uint8_t* base = (uint8_t*)ws;
   if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, c.gw_bits, 1, gy_codes, s));
   if (gy_scale) HOT_TRY(hipMemcpyAsync(gy_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(launch_igemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, g.pitch,
-                         c.gw_bits, plan_gemm(O, I, g.pitch, c.gw_bits, false), nullptr, acc, nullptr,
-                         nullptr, 0, nullptr, c.n, s));
+    HOT_TRY(gemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, c.gw_bits, base,
+                 g.partial, acc, nullptr, nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
 
-hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const void* act_buf,
+hot_status hot_debug_fused_operands(const hot_config* cfg, void* ws, const void* act_buf,
                                     int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
                                     int8_t* gy_codes, float* gy_scales, int8_t* w_codes,
                                     float* w_scale, int32_t* acc_gx, int8_t* gyT_codes,
@@ -574,13 +587,12 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, const void* ws, const
   const FusedLayout f = fused_layout(c, L, O, I);
   const ActLayout a = act_layout(c, L, I);
   hipStream_t s = (hipStream_t)stream;
-  const uint8_t* base = (const uint8_t*)ws;
+  uint8_t* base = (uint8_t*)ws;
   if (gyT_codes) HOT_TRY(launch_unpack(base + f.qgh, O, f.gw.Lr, f.gw.pitch, 8, 1, gyT_codes, s));
   if (gyT_scale) HOT_TRY(hipMemcpyAsync(gyT_scale, base + f.s_gh, 4, hipMemcpyDeviceToDevice, s));
   if (acc_gw)
-    HOT_TRY(launch_igemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, f.gw.pitch,
-                         8, plan_gemm(O, I, f.gw.pitch, 8, false), nullptr, acc_gw, nullptr, nullptr,
-                         0, nullptr, c.n, s));
+    HOT_TRY(gemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, 8, base, f.partial,
+                 acc_gw, nullptr, nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
 

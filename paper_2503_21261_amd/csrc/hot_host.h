@@ -43,37 +43,48 @@ RowTiling row_tiling(const Config& c, int64_t L);
 // K-contiguous operand rows are padded with zero codes to a multiple of 128 bytes.
 constexpr int64_t kPitchAlign = 128;
 constexpr int64_t kHeaderBytes = 256;
-// Every workspace starts with 256 bytes of scalars (scales, results) and two arrays
-// of per-workgroup partial maxima.
+// Every workspace starts with 256 bytes of scalars (scales, results), two arrays
+// of per-workgroup partial maxima and the flags of a split-K GEMM's partial sums.
 constexpr int64_t kPartialBytes = 2048 * 4;
-constexpr int64_t kWsPrefix = kHeaderBytes + 2 * kPartialBytes;
+constexpr int kMaxSplitSlots = 1024;
+constexpr int64_t kGemmFlagsOffset = kHeaderBytes + 2 * kPartialBytes;
+constexpr int64_t kWsPrefix = kGemmFlagsOffset + kMaxSplitSlots * 8;
 // |code products| summed over K must fit int32 (INT4 operands are fed to the
 // matrix cores as 16 x code, so their bound carries a factor 256).
 constexpr int64_t kMaxK8 = 133144;   // 127^2 * K < 2^31
 constexpr int64_t kMaxK4 = 171196;   // 256 * 7^2 * K < 2^31
 
-// Tile shape and K split of one GEMM launch (a pure function of the shape).
+// Tile shape and K split of one GEMM launch.
 struct GemmPlan {
-  int bm, bn, bkb, split;
+  int bm, bn, bkb;
+  int split;              // workgroups (K slices) per output tile
   int64_t tiles;
-  size_t partial_bytes;   // split > 1: tiles * split * bm * bn int32
+  size_t partial_bytes;   // split > 1: tiles * (split - 1) * bm * bn int32
 };
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_split);
+// `scratch`: a region of gemm_scratch_bytes() and the workspace's flag slots are available,
+// so K may be split.
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch);
+// Upper bound of partial_bytes over every plan of this shape (whatever mode is forced).
+size_t gemm_scratch_bytes(int64_t M, int64_t N, int64_t k_bytes, int bits);
+// Measurement / test overrides: 0 = cost model, 1 = one workgroup per tile, s >= 2 = s K
+// slices wherever a split applies; bound of the wait for another workgroup's image (0:
+// never wait).
+void set_gemm_mode(int mode);
+void set_gemm_wait_us(int us);
 
 struct GxLayout {
   int64_t pitch;                      // bytes per operand row (K = O codes)
-  size_t scalars, sg, qg, qw, total;  // byte offsets into ws
+  size_t scalars, sg, qg, qw, partial, total;  // byte offsets into ws
 };
 struct GwLayout {
   int64_t Lr, pitch;                  // reduced token count, bytes per operand row
-  GemmPlan plan;
   size_t scalars, qg, partial, total;
 };
 // hot_linear_backward: the g_x layout first (so its operand view applies unchanged),
 // then the per-token abs-max partials and the g_w operands.
 struct FusedLayout {
   GxLayout gx;
-  GwLayout gw;                        // pitch / plan only; offsets below
+  GwLayout gw;                        // pitch only; offsets below
   size_t s_gh, rowpart, qgh, partial, total;
 };
 struct SelLayout {
@@ -99,7 +110,7 @@ WeightLayout weight_layout(const Config& c, int64_t O, int64_t I);
 // Kernel roles for the optional stage timer (names in profile.hip).
 enum Stage {
   kStUnused = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
-  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStGwReduce, kStGyFusedAbsmax,
+  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStUnused2, kStGyFusedAbsmax,
   kStGyFusedQuant
 };
 void stage_begin(int stage, hipStream_t s);
@@ -157,13 +168,13 @@ void set_exchange_wait_us(int us);
 // k_bytes = K * bits / 8 rounded up to the pitch alignment).
 //   out_i32 != NULL: raw int32 accumulators, row-major [M x N].
 //   out_f32 != NULL: out = acc * row_scale[m * row_stride] * (*col_scale) / n.
-// plan.split > 1 needs `partial` (plan.partial_bytes): each K slice leaves its
-// accumulators there and a second kernel adds them in slice order.
+// plan.split > 1 needs `partial` (plan.partial_bytes) and `flags` (kMaxSplitSlots slots
+// that only such launches ever write).
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
                         int64_t pitch, int bits, const GemmPlan& plan, int32_t* partial,
-                        int32_t* out_i32, float* out_f32, const float* row_scale, int row_stride,
-                        const float* col_scale, int n, hipStream_t s, int gemm_stage = -1,
-                        int reduce_stage = -1);
+                        unsigned long long* flags, int32_t* out_i32, float* out_f32,
+                        const float* row_scale, int row_stride, const float* col_scale, int n,
+                        hipStream_t s, int gemm_stage = -1);
 
 // Unpack K-contiguous codes [rows x pitch] into one int8 per code.
 //   transpose = 0: out[row * K + k];  transpose = 1: out[k * rows + row].

@@ -1,6 +1,7 @@
-// Launchers of the integer GEMM (kernel in igemm_kernel.h), the split-K reduction and
-// the code unpacker used by the parity views.
+// Launch plan and launchers of the integer GEMM (kernel in igemm_kernel.h) and the code
+// unpacker used by the parity views.
 #include <atomic>
+#include <chrono>
 
 #include "hot_host.h"
 #include "igemm_kernel.h"
@@ -42,31 +43,63 @@ hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t 
 // Tile configurations.  Three workgroup tiles exist: 128x128 (64x64 per wave, three
 // workgroups per compute unit, so one workgroup's stores overlap the others' main
 // loops, but the INT4 widening costs 6 vector instructions per matrix instruction and
-// the vector pipe becomes the limit), 192x256 and 256x256 (96x128 / 128x128 per wave,
-// one workgroup per unit, half the widening and LDS traffic per matrix instruction, but
-// nothing hides the output stores and a partial last round idles units).  The choice
-// minimises a cost model fitted to measurements on MI355X: rounds over the 256 units
-// x (tile operations / sustained rate of that tile + unhidden store time).  INT8
-// operands (twice the bytes per operation) take 128-byte K stages.  A GEMM with a small
-// output and a long K (the g_w path) is split along K only as far as needed to give
-// every unit a workgroup: each extra slice costs an int32 image of the output in HBM.
-GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_split) {
+// the vector pipe becomes the limit; with INT8 operands its LDS traffic, 1 KB per matrix
+// instruction, is the limit), 192x256 and 256x256 (96x128 / 128x128 per wave, one workgroup
+// per unit, half the widening and LDS traffic per matrix instruction, but nothing hides the
+// output stores and a partial last round idles units).  The choice minimises a cost model
+// fitted to measurements on MI355X: rounds over the compute units x (tile operations /
+// sustained rate of that tile + unhidden store time).  INT8 operands (twice the bytes per
+// operation) take 128-byte K stages.  A GEMM with a small output and a long K (the g_w
+// path of ViT-sized layers) leaves most units idle with one workgroup per tile: its K range
+// is split over several workgroups per tile, which hand their partial sums to the last one
+// through the workspace.
+namespace {
+std::atomic<int> g_gemm_mode{0};   // 0: cost model, 1: never split K, s >= 2: s slices where possible
+std::atomic<int> g_gemm_wait_us{200};
+
+int compute_units() {
+  static std::atomic<int> cus{0};
+  int c = cus.load(std::memory_order_relaxed);
+  if (c > 0) return c;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c <= 0)
+    c = 256;   // planning only (sizes a scratch region); nothing is launched from here
+  cus.store(c, std::memory_order_relaxed);
+  return c;
+}
+
+// Most slices a 128x128-tile GEMM may be cut into: at least 4 K stages per slice, and no more
+// image slots than the workspace has flags for.
+int64_t max_split(int64_t tiles, int64_t nk) {
+  int64_t s = nk / 4;
+  if (s > 8) s = 8;
+  while (s > 1 && tiles * (s - 1) > kMaxSplitSlots) --s;
+  return s < 1 ? 1 : s;
+}
+}  // namespace
+
+void set_gemm_mode(int mode) { g_gemm_mode.store(mode); }
+void set_gemm_wait_us(int us) { g_gemm_wait_us.store(us); }
+
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch) {
   struct Cand { int bm, bn; double tops; bool hides_stores; };
   static const Cand cands4[] = {{128, 128, 1900., true}, {192, 256, 2700., false}, {256, 256, 3200., false}};
   static const Cand cands8[] = {{128, 128, 1000., true}, {256, 256, 2200., false}};
   const Cand* cands = bits == 4 ? cands4 : cands8;
   const int ncand = bits == 4 ? 3 : 2;
   const double K = (double)k_bytes * (bits == 4 ? 2 : 1);
+  const int cus = compute_units();
   GemmPlan p;
   p.split = 1;
   p.partial_bytes = 0;
   double best = 1e30;
   for (int c = 0; c < ncand; ++c) {
     const int64_t tiles = ceil_div(M, cands[c].bm) * ceil_div(N, cands[c].bn);
-    const double rounds = (double)ceil_div(tiles, 256);
+    const double rounds = (double)ceil_div(tiles, cus);
     const double ops = 2.0 * cands[c].bm * cands[c].bn * K;
-    double t = ops / (cands[c].tops * 1e12 / 256);
-    if (!cands[c].hides_stores) t += 4.0 * cands[c].bm * cands[c].bn / (5.5e12 / 256);
+    double t = ops / (cands[c].tops * 1e12 / cus);
+    if (!cands[c].hides_stores) t += 4.0 * cands[c].bm * cands[c].bn / (5.5e12 / cus);
     t *= rounds;
     if (t < best) {
       best = t;
@@ -76,57 +109,83 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool allow_s
     }
   }
   p.bkb = bits == 4 ? 64 : 128;
-  if (allow_split && p.bm == 128) {
-    int64_t s = 256 / p.tiles;
-    const int64_t nk = k_bytes / p.bkb;
-    if (s > nk / 4) s = nk / 4;   // at least 4 stages per slice
+  const int mode = g_gemm_mode.load();
+  if (scratch && bits != 16 && p.bm == 128 && mode != 1) {
+    const int64_t nk = k_bytes / p.bkb, most = max_split(p.tiles, nk);
+    // measured on MI355X (128x128 INT8 tiles, K of 50-200 stages): fastest with as many slices
+    // as keep all workgroups resident at once, two per compute unit; a partial second round
+    // costs more than the shorter slices gain
+    int64_t s = mode >= 2 ? mode : (p.tiles < cus ? 2 * cus / p.tiles : 1);
+    if (s > most) s = most;
     if (s >= 2) {
-      p.split = (int)ceil_div(nk, ceil_div(nk, s));   // no empty slice
-      p.partial_bytes = (size_t)p.tiles * p.split * 128 * 128 * 4;
+      p.split = (int)s;
+      p.partial_bytes = (size_t)p.tiles * (s - 1) * 128 * 128 * 4;
     }
   }
   return p;
 }
 
+size_t gemm_scratch_bytes(int64_t M, int64_t N, int64_t k_bytes, int bits) {
+  if (bits == 16 || M <= 0 || N <= 0) return 0;
+  const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
+  const int64_t s = max_split(tiles, k_bytes / (bits == 4 ? 64 : 128));
+  return (size_t)tiles * (s - 1) * 128 * 128 * 4;
+}
+
 namespace {
 
-template <int BM, int BN, int BKB, bool INT4, bool BF16 = false>
-hipError_t launch_tile(GemmArgs g, int64_t k_bytes, hipStream_t s, int gemm_stage, int reduce_stage) {
-  if (BF16 && g.split != 1) return hipErrorInvalidValue;
-  g.nk_total = (int)(k_bytes / BKB);
-  g.stages_per_split = (int)ceil_div(g.nk_total, g.split);
-  g.tiles_m = (int)ceil_div(g.M, BM);
-  g.tiles_n = (int)ceil_div(g.N, BN);
+uint32_t next_gemm_tag() {
+  static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() | 1u};
+  return tag.fetch_add(1, std::memory_order_relaxed);
+}
+
+template <int BM, int BN, int BKB, bool INT4, bool BF16, bool SPLITK>
+hipError_t launch_kernel(const GemmArgs& g, unsigned grid, hipStream_t s, int gemm_stage) {
   const size_t lds = 2 * (size_t)(BM + BN) * BKB;
-  auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4, BF16>;
+  auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4, BF16, SPLITK>;
   static std::atomic<bool> attr_set{false};  // per instantiation; setting it twice is harmless
   if (!attr_set.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set.store(true, std::memory_order_release);
   }
-  const dim3 grid((unsigned)((int64_t)g.tiles_m * g.tiles_n), 1, (unsigned)g.split);
   if (gemm_stage >= 0) stage_begin(gemm_stage, s);
-  kern<<<grid, dim3(256), lds, s>>>(g);
+  kern<<<dim3(grid), dim3(256), lds, s>>>(g);
   if (gemm_stage >= 0) stage_end(gemm_stage, s);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || g.split == 1) return e;
-  const unsigned blocks = (unsigned)((int64_t)g.tiles_m * g.tiles_n * (BM * BN / 256 / 16));
-  if (reduce_stage >= 0) stage_begin(reduce_stage, s);
-  splitk_image_reduce_kernel<BM, BN, 2, 2><<<dim3(blocks), dim3(256), 0, s>>>(g);
-  if (reduce_stage >= 0) stage_end(reduce_stage, s);
   return hipGetLastError();
+}
+
+template <int BM, int BN, int BKB, bool INT4, bool BF16 = false>
+hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, int gemm_stage) {
+  g.nk_total = (int)(k_bytes / BKB);
+  g.tiles_m = (int)ceil_div(g.M, BM);
+  g.tiles_n = (int)ceil_div(g.N, BN);
+  g.split = split;
+  const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
+  if (split <= 1) return launch_kernel<BM, BN, BKB, INT4, BF16, false>(g, (unsigned)tiles, s, gemm_stage);
+  if constexpr (BF16 || BM != 128) {
+    return hipErrorInvalidValue;   // only the small tile is ever split
+  } else {
+    if (!g.partial || !g.flags || tiles * (split - 1) > kMaxSplitSlots) return hipErrorInvalidValue;
+    g.tag = next_gemm_tag();
+    // an image normally arrives before its owner has finished its own slice; the bound only
+    // has to cover workgroups that start late: never less than the whole GEMM takes at 200 TOP/s
+    int64_t wait_us = g_gemm_wait_us.load();
+    const int64_t gemm_us = (int64_t)(2.0 * g.M * g.N * (double)k_bytes * (INT4 ? 2 : 1) / 200e6);
+    if (wait_us > 0 && wait_us < gemm_us) wait_us = gemm_us;
+    g.wait_ticks = wait_us < 0 ? 0 : wait_us * 100;
+    return launch_kernel<BM, BN, BKB, INT4, false, true>(g, (unsigned)(tiles * split), s, gemm_stage);
+  }
 }
 
 }  // namespace
 
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
                         int64_t pitch, int bits, const GemmPlan& plan, int32_t* partial,
-                        int32_t* out_i32, float* out_f32, const float* row_scale,
-                        int row_stride, const float* col_scale, int n, hipStream_t s,
-                        int gemm_stage, int reduce_stage) {
+                        unsigned long long* flags, int32_t* out_i32, float* out_f32,
+                        const float* row_scale, int row_stride, const float* col_scale, int n,
+                        hipStream_t s, int gemm_stage) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (plan.split > 1 && !partial) return hipErrorInvalidValue;
   GemmArgs g;
   g.A = A;
   g.B = B;
@@ -135,25 +194,27 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   g.pitch = pitch;
   g.out_i32 = out_i32;
   g.out_f32 = out_i32 ? nullptr : out_f32;  // int32 wins; callers ask one at a time
-  g.split = plan.split;
   g.partial = partial;
+  g.flags = flags;
+  g.tag = 0;
+  g.wait_ticks = 0;
   g.row_scale = row_scale;
   g.row_stride = row_stride;
   g.col_scale = col_scale;
   g.inv_n = 1.0f / (float)n;
-  const int gs = gemm_stage, rs = reduce_stage;
+  const int gs = gemm_stage, sw = plan.split;
   if (bits == 16) {
-    if (plan.bm == 256) return launch_tile<256, 256, 128, false, true>(g, k_bytes, s, gs, rs);
-    if (plan.bm == 128) return launch_tile<128, 128, 128, false, true>(g, k_bytes, s, gs, rs);
+    if (plan.bm == 256) return launch_tile<256, 256, 128, false, true>(g, k_bytes, sw, s, gs);
+    if (plan.bm == 128) return launch_tile<128, 128, 128, false, true>(g, k_bytes, sw, s, gs);
     return hipErrorInvalidValue;
   }
   if (plan.bm == 256)
-    return bits == 4 ? launch_tile<256, 256, 64, true>(g, k_bytes, s, gs, rs)
-                     : launch_tile<256, 256, 128, false>(g, k_bytes, s, gs, rs);
-  if (plan.bm == 192 && bits == 4) return launch_tile<192, 256, 64, true>(g, k_bytes, s, gs, rs);
+    return bits == 4 ? launch_tile<256, 256, 64, true>(g, k_bytes, sw, s, gs)
+                     : launch_tile<256, 256, 128, false>(g, k_bytes, sw, s, gs);
+  if (plan.bm == 192 && bits == 4) return launch_tile<192, 256, 64, true>(g, k_bytes, sw, s, gs);
   if (plan.bm == 128)
-    return bits == 4 ? launch_tile<128, 128, 64, true>(g, k_bytes, s, gs, rs)
-                     : launch_tile<128, 128, 128, false>(g, k_bytes, s, gs, rs);
+    return bits == 4 ? launch_tile<128, 128, 64, true>(g, k_bytes, sw, s, gs)
+                     : launch_tile<128, 128, 128, false>(g, k_bytes, sw, s, gs);
   return hipErrorInvalidValue;
 }
 

@@ -42,13 +42,16 @@ struct GemmArgs {
   const uint8_t* B;
   int M, N;
   int nk_total;          // K stages of BKB bytes in the whole K range
-  int stages_per_split;  // K stages handled by one blockIdx.z slice
   int64_t pitch;         // bytes per operand row
   int tiles_m, tiles_n;
   int32_t* out_i32;      // raw accumulators [M][N], or
   float* out_f32;        // dequantised output [M][N]
-  int split;             // K slices (gridDim.z); > 1: accumulators go to `partial`
-  int32_t* partial;      // [tile][slice][register image of the 256-thread tile]
+  // Split-K launches only (slot = tile * (split - 1) + slice, for all slices but the last):
+  int split;                   // K slices
+  int32_t* partial;            // [slot][register image of the 256-thread tile]
+  unsigned long long* flags;   // [slot] (tag << 32 | slot + 1) once the image is complete
+  unsigned tag;                // differs from launch to launch: slots never need clearing
+  long long wait_ticks;        // bound on the wait for another workgroup's image (100 MHz ticks)
   const float* row_scale;
   int row_stride;
   const float* col_scale;
@@ -63,11 +66,11 @@ struct GemmArgs {
 // (measured before this ordering: the A operand of the g_x GEMM was fetched once per
 // tile column, 6x its size).
 constexpr int kGroupM = 8;
-__device__ __forceinline__ void tile_of_block(const GemmArgs& g, int& tm, int& tn) {
-  const int total = g.tiles_m * g.tiles_n;
-  int id = blockIdx.x;
+__device__ __forceinline__ int xcd_contiguous(int id, int total) {
   const int per_xcd = total / 8;
-  if (id < per_xcd * 8) id = (id % 8) * per_xcd + id / 8;
+  return id < per_xcd * 8 ? (id % 8) * per_xcd + id / 8 : id;
+}
+__device__ __forceinline__ void tile_of_position(const GemmArgs& g, int id, int& tm, int& tn) {
   const int band = kGroupM * g.tiles_n;
   const int first_m = (id / band) * kGroupM;
   int rows = g.tiles_m - first_m;
@@ -96,10 +99,23 @@ struct Operands {            // what the matrix instructions of one K slice cons
 
 // BF16 = true: the same data movement with bfloat16 operands (16 bytes per lane are 8
 // elements of v_mfma_f32_32x32x16_bf16) and fp32 accumulators; the "integer" outputs then
-// carry the accumulators' fp32 bit patterns, and K cannot be split.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, bool INT4, bool BF16 = false>
+// carry the accumulators' fp32 bit patterns.
+//
+// SPLITK = false: workgroup b computes output tile b over the whole K range.
+// SPLITK = true: the K range is cut into g.split slices and the grid holds one workgroup
+// per (slice, tile), slice-major, so that workgroups running side by side work on
+// neighbouring tiles at the same K offsets and share operand tiles through L2 exactly as
+// without the split.  The workgroup of a tile's last slice owns the tile and writes its
+// output; the others leave their accumulators as a register image in `partial` and announce
+// it in `flags`.  Owners are dispatched last, so they normally find the images waiting.
+// The wait is bounded: an owner that does not see an image in time computes that slice
+// itself (integer sums do not depend on who adds what), so the kernel finishes even if
+// workgroups are not resident together.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, bool INT4, bool BF16 = false,
+          bool SPLITK = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const GemmArgs g) {
   static_assert(!(INT4 && BF16), "one operand format");
+  static_assert(!(SPLITK && BF16), "fp32 sums would depend on which workgroup added a piece");
   using acc_t = std::conditional_t<BF16, v16f, v16i>;
   constexpr int NT = 64 * WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -113,26 +129,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   static_assert(KS >= 2 && KS % 2 == 0, "pipeline needs an even number of K slices per stage");
   extern __shared__ __align__(16) uint8_t smem[];
   __shared__ float s_rowfac[BM];   // row_scale[m] * col_scale / n for the rows of this tile
+  __shared__ int s_seen;           // split-K: outcome of the wait for another workgroup's image
   uint8_t* As = smem;
   uint8_t* Bs = smem + 2 * BM * LP;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int tm, tn;
-  tile_of_block(g, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
   const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
-  const int k_begin = blockIdx.z * g.stages_per_split;
-  int k_end = k_begin + g.stages_per_split;
-  if (k_end > g.nk_total) k_end = g.nk_total;
-  const int nk = k_end - k_begin;
-  if (g.out_f32) {  // visible to every wave after the barrier that follows the first LDS stage
-    // INT4 accumulators carry an exact factor 256 (a power of two: folding it into the
-    // row factor gives the same fp32 result as shifting the integer first)
-    const float cs = (*g.col_scale) * g.inv_n * (INT4 ? 1.0f / 256.0f : 1.0f);
-    for (int i = tid; i < BM; i += NT)
-      s_rowfac[i] = m0 + i < g.M ? g.row_scale[(int64_t)(m0 + i) * g.row_stride] * cs : 0.0f;
-  }
-  __syncthreads();
 
   // LDS layout: row r of a tile holds its BKB bytes as 16-byte chunks, chunk c stored at
   // position c ^ f(r), f(r) = (r >> 1) & 3 for 64-byte rows, r & 7 for 128-byte rows.  Any
@@ -142,20 +144,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   auto swz = [](int r) { return TPR == 4 ? (r >> 1) & 3 : r & 7; };
   const int lr = tid / TPR, lseg = (tid % TPR) * 16;
   const int st_off = lr * LP + 16 * ((tid % TPR) ^ swz(lr));
+  int m0 = 0, n0 = 0;
   const uint8_t* a_src[PA];
   const uint8_t* b_src[PB];
+  auto set_tile = [&](int tm, int tn) {
+    m0 = tm * BM;
+    n0 = tn * BN;
 #pragma unroll
-  for (int p = 0; p < PA; ++p) {
-    int row = m0 + lr + RPP * p;
-    row = row < g.M ? row : g.M - 1;
-    a_src[p] = g.A + (int64_t)row * g.pitch + lseg;
-  }
+    for (int p = 0; p < PA; ++p) {
+      int row = m0 + lr + RPP * p;
+      row = row < g.M ? row : g.M - 1;
+      a_src[p] = g.A + (int64_t)row * g.pitch + lseg;
+    }
 #pragma unroll
-  for (int p = 0; p < PB; ++p) {
-    int row = n0 + lr + RPP * p;
-    row = row < g.N ? row : g.N - 1;
-    b_src[p] = g.B + (int64_t)row * g.pitch + lseg;
-  }
+    for (int p = 0; p < PB; ++p) {
+      int row = n0 + lr + RPP * p;
+      row = row < g.N ? row : g.N - 1;
+      b_src[p] = g.B + (int64_t)row * g.pitch + lseg;
+    }
+  };
+  // Row factors of the current tile; visible to every wave after the next barrier.
+  auto fill_rowfac = [&]() {
+    if (g.out_f32) {
+      // INT4 accumulators carry an exact factor 256 (a power of two: folding it into the
+      // row factor gives the same fp32 result as shifting the integer first)
+      const float cs = (*g.col_scale) * g.inv_n * (INT4 ? 1.0f / 256.0f : 1.0f);
+      for (int i = tid; i < BM; i += NT)
+        s_rowfac[i] = m0 + i < g.M ? g.row_scale[(int64_t)(m0 + i) * g.row_stride] * cs : 0.0f;
+    }
+  };
   v4i ra[PA], rb[PB];
   auto load_stage = [&](int kt) {
     const int64_t off = (int64_t)kt * BKB;
@@ -174,12 +191,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
   };
 
   acc_t acc[TM][TN];
+  auto zero_acc = [&]() {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+  };
 
   int a_off[KS], b_off[KS];  // fragment of K slice ks: chunk 2*ks + lane/32 of row lane%32
 #pragma unroll
@@ -274,8 +293,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
       __builtin_amdgcn_sched_barrier(0);
     });
   };
-
-  if (nk > 0) {
+  // acc += K stages [k_begin, k_end) of the current tile.  The caller has put a barrier
+  // between the last use of LDS and this call.
+  auto main_loop = [&](int k_begin, int k_end) {
+    const int nk = k_end - k_begin;
+    if (nk <= 0) return;
     load_stage(k_begin);
     store_stage(0);
     load_stage(k_begin + (nk > 1 ? 1 : 0));
@@ -293,102 +315,150 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const Gem
         else slice(ksc, u1, u0, cur, nxt, off2);
       });
     }
-  }
-
-  // Split-K: every slice stores its accumulators as a register image (fully coalesced);
-  // a second kernel adds the images in slice order and applies the epilogue.
-  if (g.split > 1) {
-    const int tile_id = tm * g.tiles_n + tn;
-    constexpr int IMG = BM * BN;
-    int32_t* mine = g.partial + ((int64_t)tile_id * g.split + blockIdx.z) * IMG;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if constexpr (!BF16)
-            mine[((i * TN + j) * 16 + v) * NT + tid] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
-    return;
-  }
+  };
 
   // Epilogue.  Accumulator register v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32, so each register is stored as 32-float (128-byte) row segments.
   // The row factors come from LDS (filled before the main loop): a global load per row
   // here could not be hoisted above the output stores and would serialise on L2 latency.
   // Offsets within the tile are 32-bit on top of a uniform base pointer.
-  const int nl0 = wn0 + (lane & 31);
-  if (g.out_f32) {
-    float* obase = g.out_f32 + ((int64_t)m0 * g.N + n0);
+  auto epilogue = [&]() {
+    // Split-K runs this after loops: an opaque copy of the lane index keeps the compiler
+    // from hoisting the ~100 output addresses out of them (they would be live, in
+    // registers, across the main loop).
+    int ln = lane;
+    if constexpr (SPLITK) asm volatile("" : "+v"(ln));
+    const int lane = ln;
+    const int nl0 = wn0 + (lane & 31);
+    if (g.out_f32) {
+      float* obase = g.out_f32 + ((int64_t)m0 * g.N + n0);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m0 + ml >= g.M) continue;
-        const float rs = s_rowfac[ml];
-        const int row_off = ml * g.N + nl0;
+        for (int v = 0; v < 16; ++v) {
+          const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (m0 + ml >= g.M) continue;
+          const float rs = s_rowfac[ml];
+          const int row_off = ml * g.N + nl0;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          if (n0 + nl0 + j * 32 < g.N) obase[row_off + j * 32] = (float)acc[i][j][v] * rs;
+          for (int j = 0; j < TN; ++j)
+            if (n0 + nl0 + j * 32 < g.N) obase[row_off + j * 32] = (float)acc[i][j][v] * rs;
+        }
+      }
+    } else {
+      int32_t* obase = g.out_i32 + ((int64_t)m0 * g.N + n0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (m0 + ml >= g.M) continue;
+          const int row_off = ml * g.N + nl0;
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            if (n0 + nl0 + j * 32 < g.N) {
+              if constexpr (BF16) obase[row_off + j * 32] = __float_as_int(acc[i][j][v]);
+              else obase[row_off + j * 32] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
+            }
+        }
       }
     }
-  } else {
-    int32_t* obase = g.out_i32 + ((int64_t)m0 * g.N + n0);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ml = wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (m0 + ml >= g.M) continue;
-        const int row_off = ml * g.N + nl0;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          if (n0 + nl0 + j * 32 < g.N) {
-            if constexpr (BF16) obase[row_off + j * 32] = __float_as_int(acc[i][j][v]);
-            else obase[row_off + j * 32] = INT4 ? (acc[i][j][v] >> 8) : acc[i][j][v];
-          }
-      }
-    }
-  }
-}
+  };
 
-// Second half of a split-K GEMM: out[m][n] = epilogue(sum over slices of the register
-// images the GEMM left), slices added in order (exact in int32).  One workgroup handles
-// 16 of the 16*TM*TN accumulator registers of one tile; reads and writes are the same
-// coalesced patterns the GEMM itself uses.
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(256) void splitk_image_reduce_kernel(const GemmArgs g) {
-  constexpr int NT = 64 * WAVES_M * WAVES_N;
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  constexpr int TN = WN / 32;
-  constexpr int IMG = BM * BN;
-  constexpr int QPB = 16;                       // registers per workgroup
-  constexpr int BPT = IMG / NT / QPB;           // workgroups per tile
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int tile_id = blockIdx.x / BPT, q0 = (blockIdx.x % BPT) * QPB;
-  const int tm = tile_id / g.tiles_n, tn = tile_id % g.tiles_n;
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
-  const float cs = g.out_f32 ? (*g.col_scale) * g.inv_n : 0.0f;
-  const int32_t* img = g.partial + (int64_t)tile_id * g.split * IMG;
-  int sum[QPB];
+  if constexpr (!SPLITK) {
+    int tm, tn;
+    tile_of_position(g, xcd_contiguous(blockIdx.x, g.tiles_m * g.tiles_n), tm, tn);
+    set_tile(tm, tn);
+    fill_rowfac();
+    zero_acc();
+    main_loop(0, g.nk_total);   // has a barrier when there is any stage; else acc = 0 ...
+    if (g.nk_total <= 0) __syncthreads();   // ... and the row factors still need one
+    epilogue();
+  } else {
+    constexpr int IMG = BM * BN;
+    const int tiles = g.tiles_m * g.tiles_n, nk = g.nk_total, S = g.split;
+    const int z = blockIdx.x / tiles;   // slices in dispatch order: owners (z = S - 1) start last
+    int tm, tn;
+    const int t = xcd_contiguous(blockIdx.x - z * tiles, tiles);
+    tile_of_position(g, t, tm, tn);
+    auto slice_begin = [&](int zz) { return (int)(((int64_t)zz * nk) / S); };
+    const bool owned = z == S - 1;
+    set_tile(tm, tn);
+    if (owned) fill_rowfac();
+    zero_acc();
+    // own slice first, then the earlier ones: taken from their workgroups' images, or, when
+    // one does not show up in time, computed here
+    int zz = z;
+    while (true) {
+      main_loop(slice_begin(zz), slice_begin(zz + 1));
+      bool more = false;
+      while (owned && zz > 0) {
+        --zz;
+        const int slot = t * (S - 1) + zz;
+        if (tid == 0) {
+          const unsigned long long want = ((unsigned long long)g.tag << 32) | (unsigned)(slot + 1);
+          const long long start = wall_clock64();
+          bool seen;
+          do {
+            seen = __hip_atomic_load(&g.flags[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == want;
+          } while (!seen && wall_clock64() - start < g.wait_ticks);
+          s_seen = seen;
+        }
+        __syncthreads();
+        const bool seen = s_seen != 0;
+        __syncthreads();   // everyone has read s_seen before it can be rewritten
+        if (!seen) { more = true; break; }
+        // up to four 32x32 tiles' worth of loads in flight at a time (one memory round trip
+        // for the 128x128 tile; more would not fit next to the larger tiles' accumulators)
+        int t_img = tid;
+        asm volatile("" : "+v"(t_img));   // addresses are computed here, not before the loop
+        const int32_t* img = g.partial + (int64_t)slot * IMG + t_img;
+        constexpr int QG = TM * TN < 4 ? TM * TN : 4;
+        static_assert(TM * TN % QG == 0, "groups of accumulator tiles");
+        static_for<TM * TN / QG>([&](auto gc) {
+          constexpr int q0 = decltype(gc)::value * QG;
+          int part[QG][16];
 #pragma unroll
-  for (int k = 0; k < QPB; ++k) sum[k] = 0;
-  for (int z = 0; z < g.split; ++z, img += IMG) {
+          for (int q = 0; q < QG; ++q)
 #pragma unroll
-    for (int k = 0; k < QPB; ++k) sum[k] += img[(q0 + k) * NT + tid];
-  }
+            for (int v = 0; v < 16; ++v)
+              part[q][v] = __hip_atomic_load(&img[((q0 + q) * 16 + v) * NT], __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-  for (int k = 0; k < QPB; ++k) {
-    const int q = q0 + k;
-    const int v = q & 15, j = (q >> 4) % TN, i = (q >> 4) / TN;
-    const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-    const int n = n0 + wn0 + j * 32 + (lane & 31);
-    if (m < g.M && n < g.N) {
-      const int64_t o = (int64_t)m * g.N + n;
-      if (g.out_f32) g.out_f32[o] = (float)sum[k] * (g.row_scale[(int64_t)m * g.row_stride] * cs);
-      else g.out_i32[o] = sum[k];
+          for (int q = 0; q < QG; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[(q0 + q) / TN][(q0 + q) % TN][v] += part[q][v];
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      }
+      if (!more) break;
+      __syncthreads();   // LDS of the last main loop is free again
+    }
+    if (owned) {
+      if (nk < S) __syncthreads();   // no slice had a stage (and so no barrier) of its own
+      epilogue();
+    } else {
+      const int slot = t * (S - 1) + z;
+      int t_img = tid;
+      asm volatile("" : "+v"(t_img));
+      int32_t* mine = g.partial + (int64_t)slot * IMG + t_img;
+      static_for<TM * TN>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __hip_atomic_store(&mine[(q * 16 + v) * NT], acc[q / TN][q % TN][v], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // Image and flag travel as device-scope accesses that bypass the per-XCD L2, so no
+      // cache-wide write-back or invalidate (which would also evict every workgroup's
+      // operand tiles) is needed: the flag is stored once every thread's image stores have
+      // been acknowledged.
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (tid == 0)
+        __hip_atomic_store(&g.flags[slot], ((unsigned long long)g.tag << 32) | (unsigned)(slot + 1),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

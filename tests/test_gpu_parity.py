@@ -586,6 +586,48 @@ def test_config2_two_pass_column_kernels(exchange_wait):
     check_gw(hot, cfg, gy, x, "cfg2 two-pass")
 
 
+# ---- GEMM work distribution: one workgroup per tile and K splits must give the same integers ----
+
+@pytest.fixture
+def gemm_mode():
+    hot = _hot()
+    yield hot.hot_debug_set_gemm_mode
+    hot.hot_debug_set_gemm_mode(0)
+    hot.hot_debug_set_exchange_wait_us(200)
+
+
+@pytest.mark.parametrize("mode,wait_us", [(1, 200), (2, 200), (3, 200), (8, 200), (2, 0), (5, 0)])
+def test_gemm_work_distribution(gemm_mode, mode, wait_us):
+    """mode 1: a workgroup per output tile; mode s >= 2: K cut into s slices whose
+    workgroups hand partial sums to the tile's last one through the workspace; wait 0: no
+    owner ever waits, every missing slice is computed by the owner itself (what happens when
+    the other workgroup is late).  Shapes: few tiles with long K, many tiles, ragged tiles,
+    K too short to split."""
+    hot = _hot()
+    gemm_mode(mode)
+    hot.hot_debug_set_exchange_wait_us(wait_us)
+    for (L, O, I, n, r) in [(2048, 300, 140, 16, 8), (8192, 256, 128, 32, 16), (4096, 1056, 520, 32, 16),
+                            (512, 96, 80, 32, 16), (16384, 64, 64, 16, 8)]:
+        x, w, gy = make(L, O, I, seed=43)
+        cfg = hot.Config(block=n, keep=r)
+        check_gw(hot, cfg, gy, x, f"gemm mode={mode} wait={wait_us}")
+        if O % n == 0:
+            check_gx(hot, cfg, gy, w, True, f"gemm mode={mode} wait={wait_us}")
+            check_gx(hot, hot.Config(block=n, keep=r, gx_bits=8), gy, w, False, f"gemm mode={mode} wait={wait_us}")
+
+
+@pytest.mark.parametrize("mode,wait_us", [(3, 200), (4, 0)])
+def test_config2_split_k(gemm_mode, mode, wait_us):
+    hot = _hot()
+    gemm_mode(mode)
+    hot.hot_debug_set_exchange_wait_us(wait_us)
+    wl = hot_inputs.WORKLOADS["cfg2_vitb_fc1"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    check_gx(hot, cfg, gy, w, True, "cfg2 split-K")
+    check_gw(hot, cfg, gy, x, "cfg2 split-K")
+
+
 # ---- maximum reduction lengths: accumulators at the edge of int32 ------------------------
 
 def _hadamard_np(n):
