@@ -464,6 +464,15 @@ constexpr int kOnepassMaxKept = 160;
 template <int N, int VEC, int KIND>
 constexpr size_t onepass_stage_bytes() { return (size_t)kept_vals<N, KIND>() * 256 * VEC * 4; }
 
+// Whether a lane of the single-pass kernel stores its codes straight from registers: the
+// kept list is known at compile time and the lane's KB blocks give at least 48 consecutive
+// output bytes (shorter runs are cheaper to gather through the LDS tile).
+template <int N, int KIND, int KB>
+constexpr bool onepass_direct_store() {
+  if constexpr (KIND == kKeepGeneric) return false;
+  else return static_bpb<N, KIND>() % 8 == 0 && KB * static_bpb<N, KIND>() >= 48;
+}
+
 template <int N, int VEC, int KIND, int KB>
 __global__ __launch_bounds__(256, 2)
 void col_quant_onepass_kernel(
@@ -621,8 +630,7 @@ void col_quant_onepass_kernel(
   // A lane's codes of consecutive blocks are consecutive bytes of its column's output row:
   // with enough of them (and a compile-time kept list) they are stored straight from
   // registers, 16 or 8 bytes at a time; otherwise they go through the LDS tile.
-  constexpr bool kDirect = KIND != kKeepGeneric && static_bpb<N, KIND>() % 8 == 0 &&
-                           KB * static_bpb<N, KIND>() >= 48;
+  constexpr bool kDirect = onepass_direct_store<N, KIND, KB>();
   if constexpr (kDirect) {
     constexpr int BPB = static_bpb<N, KIND>();
     auto emit = [&](auto rounding_c) {
