@@ -35,6 +35,7 @@ def stage_model(L, O, I, n, r, gx_bits, per_token, gw_bits=8, Lr=None):
         "w_col_absmax": dict(bound="hbm", bytes=4 * O * I),
         "w_col_quant": dict(bound="hbm", bytes=4 * O * I + cb * O * I),
         "gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L),
+        "w_and_gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L + 4 * O * I + cb * O * I),
         "gy_row_absmax": dict(bound="hbm", bytes=4 * L * O),
         "gy_row_quant2": dict(bound="hbm", bytes=4 * L * O + cb * L * O),
         "gyT_col_absmax": dict(bound="hbm", bytes=4 * L * O),
@@ -170,7 +171,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="repeat the oracle on the sample until about this much CPU wall time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--backward", default="auto", choices=["auto", "separate", "shared"],
+    ap.add_argument("--backward", default="auto", choices=["auto", "separate", "shared", "unfused"],
                     help="how hot_linear_backward produces the two views of g_y: the library's "
                          "choice (default), always the two separate paths, or the shared g_y "
                          "passes wherever they exist")
@@ -209,7 +210,7 @@ def main() -> int:
     wl = hot_inputs.WORKLOADS[args.workload]
     hot.hot_debug_set_gemm_mode(args.gemm)
     if args.sweep:
-        hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2}[args.backward])
+        hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2, "unfused": 3}[args.backward])
         run_sweep(torch, hot, hot_inputs, wl, args.quantizer)   # warm-up: code objects, allocator
         print(json.dumps(run_sweep(torch, hot, hot_inputs, wl, args.quantizer)))
         return 0
@@ -226,7 +227,7 @@ def main() -> int:
     gw = torch.empty((O, I), device="cuda")
     q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
     stream = torch.cuda.current_stream()
-    hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2}[args.backward])
+    hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2, "unfused": 3}[args.backward])
 
     def step():
         hot.hot_compress_activation(cfg, x, act, ws, stream=stream)

@@ -206,7 +206,10 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, void* ws, const void*
 
 /* Strategy of hot_linear_backward: 0 = chosen by the library (default), 1 = always the two
  * separate paths, 2 = the shared passes over g_y whenever they exist (block sizes 16 and
- * 32, INT8 g_w operands, one run of tokens).  Results do not depend on it.  Process-wide. */
+ * 32, INT8 g_w operands, one run of tokens), 3 = the separate paths with every kernel in a
+ * launch of its own (by default the g_x path quantises small weights and the per-token g_y
+ * operand in one combined launch; the setting also applies to hot_linear_backward_gx).
+ * Results do not depend on it.  Process-wide. */
 hot_status hot_debug_set_backward_strategy(int strategy);
 
 /* Tensors small enough to stay in the register files of the resident workgroups (x and

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhot.so")
-SOURCES = ["api.hip", "row_quant.hip", "col_quant.hip", "col_bf16.hip", "gy_fused.hip", "igemm.hip", "select.hip", "profile.hip", "probe.hip"]
+SOURCES = ["api.hip", "row_quant.hip", "col_quant.hip", "gx_front.hip", "col_bf16.hip", "gy_fused.hip", "igemm.hip", "select.hip", "profile.hip", "probe.hip"]
 
 # IEEE fp32 is part of the contract: the integer codes depend on every add, mul and
 # div rounding exactly once, so no contraction, no fast-math, correctly rounded

@@ -150,7 +150,8 @@ bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
 }
 
 // How hot_linear_backward produces the two views of g_y: 0 = by measurement (below),
-// 1 = always the two separate paths, 2 = the shared passes whenever they exist.
+// 1 = always the two separate paths, 2 = the shared passes whenever they exist, 3 = the
+// separate paths with every kernel in a launch of its own (no combined weight / g_y launch).
 std::atomic<int> g_backward_strategy{0};
 
 bool shared_gy_passes_exist(const Config& c) {
@@ -165,7 +166,7 @@ bool shared_gy_passes_exist(const Config& c) {
 bool shared_gy_passes(const Config& c, int64_t L, int64_t O) {
   if (!shared_gy_passes_exist(c)) return false;
   const int strategy = g_backward_strategy.load();
-  if (strategy == 1) return false;
+  if (strategy == 1 || strategy == 3) return false;
   if (strategy == 2) return true;
   const int64_t kept_bytes = row_tiling(c, L).nblk * c.r * O * 4;
   return c.n == 16 && kept_bytes > 80ll * 1000 * 1000;
@@ -309,12 +310,14 @@ hipError_t gemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_
 // g_y, multiply, dequantise.
 hot_status run_gx(const Config& c, const float* g_y, const uint8_t* qw, const float* s_w, int64_t L,
                   int64_t O, int64_t I, hot_quantizer gy_quantizer, float* g_x, uint8_t* base,
-                  const GxLayout& g, hipStream_t s) {
+                  const GxLayout& g, hipStream_t s, bool rows_done = false) {
   float* part_g = (float*)(base + kHeaderBytes + kPartialBytes);
   float* s_g = (float*)(base + g.sg);
   uint8_t* qg = base + g.qg;
   int npart = 0;
-  if (gy_quantizer == HOT_Q_PER_TOKEN) {
+  if (rows_done) {
+    // the quantised g_y is already in place (combined launch with the weights)
+  } else if (gy_quantizer == HOT_Q_PER_TOKEN) {
     HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, part_g, &npart, s));
   } else {
     HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
@@ -344,10 +347,16 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   float* s_w = (float*)(base + g.scalars);
   float* part_w = (float*)(base + kHeaderBytes);
   uint8_t* qw = base + g.qw;
-  // H.w along O, one scale, written as [I x O] code rows
-  HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
-                           part_w, s, kStWAbsmax, kStWQuant));
-  return run_gx(c, g_y, qw, s_w, L, O, I, gy_quantizer, g_x, base, g, s);
+  // H.w along O, one scale, written as [I x O] code rows: together with the per-token
+  // g_y operand in one launch where that exists, else on its own
+  bool both = false;
+  if (gy_quantizer == HOT_Q_PER_TOKEN && g_backward_strategy.load() != 3)
+    HOT_TRY(launch_w_and_rows(w, O, I, c, qw, g.pitch, s_w, part_w, g_y, L, base + g.qg,
+                              (float*)(base + g.sg), s, kStWGyRow, &both));
+  if (!both)
+    HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
+                             part_w, s, kStWAbsmax, kStWQuant));
+  return run_gx(c, g_y, qw, s_w, L, O, I, gy_quantizer, g_x, base, g, s, both);
 }
 
 hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
@@ -494,7 +503,7 @@ hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_bu
 }
 
 hot_status hot_debug_set_backward_strategy(int strategy) {
-  if (strategy < 0 || strategy > 2) return HOT_ERR_ARG;
+  if (strategy < 0 || strategy > 3) return HOT_ERR_ARG;
   g_backward_strategy.store(strategy);
   return HOT_OK;
 }

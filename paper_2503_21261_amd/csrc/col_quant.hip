@@ -22,6 +22,8 @@ uint32_t next_tag() {
 }  // namespace
 
 void set_exchange_wait_us(int us) { g_exchange_wait_us.store(us); }
+int exchange_wait_us() { return g_exchange_wait_us.load(); }
+uint32_t next_exchange_tag() { return next_tag(); }
 
 ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity) {
   ColPlan p;
@@ -125,9 +127,10 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool direct_only
     const int64_t stream_us = a.rows.nblk * N * a.C * 4 / 1000000;
     if (wait_us > 0 && wait_us < stream_us) wait_us = stream_us;
     stage_begin(sq, s);
-    kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(
-        a.x, a.rows, a.C, a.map, a.r, a.rounding, reinterpret_cast<unsigned long long*>(a.partials),
-        next_tag(), (long long)(wait_us * 100), a.codes, a.pitch, a.scale);
+    const OnepassArgs oa{a.x, a.rows, a.C, a.map, a.r, a.rounding,
+                         reinterpret_cast<unsigned long long*>(a.partials), next_tag(),
+                         (long long)(wait_us * 100), a.codes, a.pitch, a.scale};
+    kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(oa);
     stage_end(sq, s);
     *done = true;
     return hipGetLastError();

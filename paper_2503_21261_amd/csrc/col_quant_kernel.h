@@ -460,9 +460,10 @@ constexpr int onepass_depth() { return (KB > 1 && onepass_kept_regs<N, VEC, KIND
 constexpr int kOnepassMaxKept = 160;
 
 // Bytes of dynamic LDS: the code tile, or (before the tile is filled) one column of
-// per-thread staging for the recomputation of another workgroup's maximum.
+// per-lane staging for the recomputation of another workgroup's maximum, used by one wave
+// at a time (that path is rare; a small footprint keeps more workgroups per compute unit).
 template <int N, int VEC, int KIND>
-constexpr size_t onepass_stage_bytes() { return (size_t)kept_vals<N, KIND>() * 256 * VEC * 4; }
+constexpr size_t onepass_stage_bytes() { return (size_t)kept_vals<N, KIND>() * 64 * VEC * 4; }
 
 // Whether a lane of the single-pass kernel stores its codes straight from registers: the
 // kept list is known at compile time and the lane's KB blocks give at least 48 consecutive
@@ -473,12 +474,36 @@ constexpr bool onepass_direct_store() {
   else return static_bpb<N, KIND>() % 8 == 0 && KB * static_bpb<N, KIND>() >= 48;
 }
 
+// Arguments of the single-pass kernel.
+struct OnepassArgs {
+  const float* x;
+  RowTiling rt;
+  int64_t C;
+  KeepMap map;
+  int r, rounding;
+  unsigned long long* slots;
+  uint32_t tag;
+  long long wait_ticks;
+  uint8_t* codes;
+  int64_t pitch;
+  float* scale;
+};
+
+// Body of the single-pass kernel for workgroup `bid` of `nbid` (the whole grid, or the
+// leading part of a grid whose other workgroups do unrelated work).
 template <int N, int VEC, int KIND, int KB>
-__global__ __launch_bounds__(256, 2)
-void col_quant_onepass_kernel(
-    const float* __restrict__ x, RowTiling rt, int64_t C, KeepMap map, int r, int rounding,
-    unsigned long long* __restrict__ slots, uint32_t tag, long long wait_ticks,
-    uint8_t* __restrict__ codes, int64_t pitch, float* __restrict__ scale) {
+__device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid, const int nbid) {
+  const float* __restrict__ x = a.x;
+  const RowTiling rt = a.rt;
+  const int64_t C = a.C;
+  const KeepMap& map = a.map;
+  const int r = a.r, rounding = a.rounding;
+  unsigned long long* __restrict__ slots = a.slots;
+  const uint32_t tag = a.tag;
+  const long long wait_ticks = a.wait_ticks;
+  uint8_t* __restrict__ codes = a.codes;
+  const int64_t pitch = a.pitch;
+  float* __restrict__ scale = a.scale;
   constexpr int CT = 64 * VEC;
   constexpr int BITS = KIND == kKeepAll4 ? 4 : 8;
   constexpr int QMAX = (1 << (BITS - 1)) - 1;
@@ -490,7 +515,7 @@ void col_quant_onepass_kernel(
   const int TB = 4 * KB * bpb, TBP = TB + 4;
   const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
-  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  const int64_t tx = bid % tiles_x, ty = bid / tiles_x;
   const int64_t c0 = tx * CT + lane * VEC;
   const bool col_ok = c0 < C;
 
@@ -541,7 +566,7 @@ void col_quant_onepass_kernel(
   }
   m = workgroup_max(m);
   if (tid == 0)
-    __hip_atomic_store(&slots[blockIdx.x], ((unsigned long long)tag << 32) | __float_as_uint(m),
+    __hip_atomic_store(&slots[bid], ((unsigned long long)tag << 32) | __float_as_uint(m),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid < 64) s_miss[tid] = 0u;
   if (tid == 0) s_nmiss = 0;
@@ -550,8 +575,8 @@ void col_quant_onepass_kernel(
   // collect the other workgroups' maxima, waiting a bounded time for each
   const long long t0 = wall_clock64();
   float amax = m;
-  for (int b = tid; b < (int)gridDim.x; b += 256) {
-    if (b == (int)blockIdx.x) continue;
+  for (int b = tid; b < nbid; b += 256) {
+    if (b == bid) continue;
     bool got = false;
     for (int polls = 0; polls < (1 << 16); ++polls) {   // second bound, should the clock stall
       const unsigned long long sv =
@@ -574,58 +599,63 @@ void col_quant_onepass_kernel(
     // a time in a rolled loop and staged in this thread's own LDS column (the code tile is
     // not in use yet), then transformed from there.
     constexpr int NS = kept_vals<N, KIND>();
-    float* stage = reinterpret_cast<float*>(tile) + tid * VEC;
-    for (int b = 0; b < (int)gridDim.x; ++b) {
-      if (!((s_miss[b >> 5] >> (b & 31)) & 1u)) continue;
-      const int64_t btx = b % tiles_x, bty = b / tiles_x;
-      const int64_t bc0 = btx * CT + lane * VEC;
-      if (bc0 >= C) continue;
-      for (int kb = 0; kb < KB; ++kb) {
-        const int64_t gb = bty * 4 * KB + w * KB + kb;
-        if (gb >= nblk) break;
-        int64_t first;
-        int valid;
-        block_rows<N>(rt, gb, first, valid);
-        const float* src = x + first * C + bc0;
-        auto row = [&](int k, float (&o)[VEC]) {   // zero padding past the sample's last token
-          if (k < valid) {
-            unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)k * C), o);
-          } else {
+    float* stage = reinterpret_cast<float*>(tile) + lane * VEC;
+    for (int turn = 0; turn < 4; ++turn) {   // the four waves take turns at the staging column
+      if (turn == w) {
+        for (int b = 0; b < nbid; ++b) {
+          if (!((s_miss[b >> 5] >> (b & 31)) & 1u)) continue;
+          const int64_t btx = b % tiles_x, bty = b / tiles_x;
+          const int64_t bc0 = btx * CT + lane * VEC;
+          if (bc0 >= C) continue;
+          for (int kb = 0; kb < KB; ++kb) {
+            const int64_t gb = bty * 4 * KB + w * KB + kb;
+            if (gb >= nblk) break;
+            int64_t first;
+            int valid;
+            block_rows<N>(rt, gb, first, valid);
+            const float* src = x + first * C + bc0;
+            auto row = [&](int k, float (&o)[VEC]) {   // zero padding past the sample's last token
+              if (k < valid) {
+                unpack_vec<VEC>(*reinterpret_cast<const VT*>(src + (int64_t)k * C), o);
+              } else {
 #pragma unroll
-            for (int vi = 0; vi < VEC; ++vi) o[vi] = 0.0f;
-          }
-        };
+                for (int vi = 0; vi < VEC; ++vi) o[vi] = 0.0f;
+              }
+            };
 #pragma unroll 1
-        for (int j = 0; j < NS; ++j) {
-          float a[VEC];
-          if constexpr (KIND == kKeepLowHalf) {
-            float lo[VEC], hi[VEC];
-            row(2 * j, lo);
-            row(2 * j + 1, hi);
+            for (int j = 0; j < NS; ++j) {
+              float a[VEC];
+              if constexpr (KIND == kKeepLowHalf) {
+                float lo[VEC], hi[VEC];
+                row(2 * j, lo);
+                row(2 * j + 1, hi);
 #pragma unroll
-            for (int vi = 0; vi < VEC; ++vi) a[vi] = lo[vi] + hi[vi];
-          } else {
-            row(j, a);
+                for (int vi = 0; vi < VEC; ++vi) a[vi] = lo[vi] + hi[vi];
+              } else {
+                row(j, a);
+              }
+#pragma unroll
+              for (int vi = 0; vi < VEC; ++vi) stage[j * 64 * VEC + vi] = a[vi];
+            }
+            float t[VEC][NS];
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+#pragma unroll
+              for (int vi = 0; vi < VEC; ++vi) t[vi][j] = stage[j * 64 * VEC + vi];
+            }
+#pragma unroll
+            for (int vi = 0; vi < VEC; ++vi) fwht_regs<NS>(t[vi]);
+            amax = fmaxf(amax, kept_form_absmax<N, VEC, KIND>(t, map));
           }
-#pragma unroll
-          for (int vi = 0; vi < VEC; ++vi) stage[j * 256 * VEC + vi] = a[vi];
         }
-        float t[VEC][NS];
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-#pragma unroll
-          for (int vi = 0; vi < VEC; ++vi) t[vi][j] = stage[j * 256 * VEC + vi];
-        }
-#pragma unroll
-        for (int vi = 0; vi < VEC; ++vi) fwht_regs<NS>(t[vi]);
-        amax = fmaxf(amax, kept_form_absmax<N, VEC, KIND>(t, map));
       }
+      __syncthreads();
     }
     __syncthreads();   // staging done before the tile is zeroed / filled
   }
   amax = workgroup_max(amax);
   const float inv = quant_inv(amax, QMAX);
-  if (blockIdx.x == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
+  if (bid == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
 
   // A lane's codes of consecutive blocks are consecutive bytes of its column's output row:
   // with enough of them (and a compile-time kept list) they are stored straight from
@@ -686,6 +716,11 @@ void col_quant_onepass_kernel(
     __syncthreads();
     write_out_tile<VEC>(tile, TB, TBP, tx, ty, nblk, KB, C, pitch, codes);
   }
+}
+
+template <int N, int VEC, int KIND, int KB>
+__global__ __launch_bounds__(256, 2) void col_quant_onepass_kernel(const OnepassArgs a) {
+  onepass_body<N, VEC, KIND, KB>(a, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Columns per lane of the single-pass kernel: two for 16-row blocks, else one.

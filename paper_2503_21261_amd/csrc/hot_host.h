@@ -110,7 +110,7 @@ WeightLayout weight_layout(const Config& c, int64_t O, int64_t I);
 // Kernel roles for the optional stage timer (names in profile.hip).
 enum Stage {
   kStUnused = 0, kStActAbsmax, kStActQuant, kStWAbsmax, kStWQuant, kStGyRowQuant, kStGyRowAbsmax,
-  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStUnused2, kStGyFusedAbsmax,
+  kStGyRowQuant2, kStGxGemm, kStGyTAbsmax, kStGyTQuant, kStGwGemm, kStWGyRow, kStGyFusedAbsmax,
   kStGyFusedQuant
 };
 void stage_begin(int stage, hipStream_t s);
@@ -161,8 +161,20 @@ hipError_t launch_gy_fused(const float* g_y, int64_t L, int64_t O, const Config&
 hipError_t launch_col_bf16(const float* x, const RowTiling& rows, int64_t C, const Config& cfg, uint8_t* out,
                            int64_t pitch, float* scale, hipStream_t s, int stage);
 
-// Bounded wait of the single-pass column kernel (microseconds; < 0: always two passes).
+// Bounded wait of the single-pass column kernel (microseconds; < 0: always two passes), and
+// the launch tags of its abs-max exchange (never repeated while stale slots may survive).
 void set_exchange_wait_us(int us);
+int exchange_wait_us();
+uint32_t next_exchange_tag();
+
+// Both operands of the g_x GEMM from one launch, where that exists (INT4, per-token g_y
+// scales, weights small enough for the single-pass column kernel, O between 257 and 4096):
+// Q(H.w) as [I x pitch] code rows with *s_w, and the rotated, per-token quantised g_y as
+// [L x pitch] code rows with s_g[L].  `slots`: kMaxPartials floats of scratch.  *done says
+// whether the launch was made; when not, nothing was written.
+hipError_t launch_w_and_rows(const float* w, int64_t O, int64_t I, const Config& cfg, uint8_t* qw,
+                             int64_t pitch, float* s_w, float* slots, const float* g_y, int64_t L,
+                             uint8_t* qg, float* s_g, hipStream_t s, int stage, bool* done);
 
 // C[M x N] = A[M x K] . B[N x K]^T on K-contiguous code rows (pitch bytes each,
 // k_bytes = K * bits / 8 rounded up to the pitch alignment).

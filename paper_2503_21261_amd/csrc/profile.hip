@@ -48,7 +48,7 @@ void stage_end(int stage, hipStream_t s) {
 const char* const kStageNames[HOT_NUM_STAGES] = {
     "unused",        "act_col_absmax", "act_col_quant", "w_col_absmax",  "w_col_quant",
     "gy_row_quant",  "gy_row_absmax",  "gy_row_quant2", "gx_igemm",      "gyT_col_absmax",
-    "gyT_col_quant", "gw_igemm",       "(unused)", "gy_fused_absmax", "gy_fused_quant"};
+    "gyT_col_quant", "gw_igemm",       "w_and_gy_row_quant", "gy_fused_absmax", "gy_fused_quant"};
 
 }  // namespace hot
 

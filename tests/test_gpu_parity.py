@@ -586,6 +586,28 @@ def test_config2_two_pass_column_kernels(exchange_wait):
     check_gw(hot, cfg, gy, x, "cfg2 two-pass")
 
 
+def test_gx_combined_and_separate_launches_agree():
+    """By default small weights and the per-token g_y operand are quantised in one launch;
+    strategy 3 gives every kernel its own launch.  Codes, scales and g_x must be the same
+    bits, with the exchange of the weight workgroups both waited for and skipped."""
+    hot = _hot()
+    try:
+        for (L, O, I, n) in [(2048, 768, 768, 32), (1024, 3072, 768, 32), (788, 512, 1024, 16), (4096, 4096, 256, 64),
+                             (512, 1024, 128, 16)]:
+            x, w, gy = make(L, O, I, seed=53)
+            cfg = hot.Config(block=n, keep=n // 2)
+            outs = []
+            for strategy, wait in [(0, 200), (3, 200), (0, 0)]:
+                hot.hot_debug_set_backward_strategy(strategy)
+                hot.hot_debug_set_exchange_wait_us(wait)
+                ref, gx = check_gx(hot, cfg, gy, w, True, f"strategy={strategy} wait={wait}")
+                outs.append(gx.clone())
+            assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    finally:
+        hot.hot_debug_set_backward_strategy(0)
+        hot.hot_debug_set_exchange_wait_us(200)
+
+
 # ---- GEMM work distribution: one workgroup per tile and K splits must give the same integers ----
 
 @pytest.fixture
