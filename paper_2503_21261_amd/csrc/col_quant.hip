@@ -86,7 +86,7 @@ hipError_t launch_quant(const ColArgs& a, const ColPlan& p, hipStream_t s) {
 // Single-pass launch with KB blocks per wave; *done stays false (nothing launched) when
 // that grid would not be resident all at once or the lane would hold too many values.
 template <int N, int KIND, int KB>
-hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool direct_only, bool* done) {
+hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, int round, bool* done) {
   constexpr int VEC = onepass_vec(N);
   if constexpr (onepass_kept_regs<N, VEC, KIND, KB>() > kOnepassMaxKept) {
     return hipSuccess;
@@ -94,9 +94,12 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool direct_only
     if (*done || a.C % VEC != 0) return hipSuccess;
     const int bpb = KIND == kKeepGeneric ? a.r : (KIND == kKeepAll8 ? N : N / 2);
     const int64_t tiles = ceil_div(a.C, 64 * VEC) * ceil_div(a.rows.nblk, 4 * KB);
-    // first round: only launch shapes whose lanes store their codes straight from registers
-    // and that still give every compute unit more than one workgroup
+    // rounds 0 and 1: only launch shapes whose lanes store their codes straight from
+    // registers (round 0: in runs that fill whole 128-byte lines per workgroup) and that
+    // still give every compute unit more than one workgroup
+    const bool direct_only = round < 2;
     if (direct_only && !onepass_direct_store<N, KIND, KB>()) return hipSuccess;
+    if (round == 0 && !onepass_whole_lines<N, KIND, KB>()) return hipSuccess;
     size_t lds = (size_t)(64 * VEC) * (4 * KB * bpb + 4);
     if (lds < onepass_stage_bytes<N, VEC, KIND>()) lds = onepass_stage_bytes<N, VEC, KIND>();
     auto kern = col_quant_onepass_kernel<N, VEC, KIND, KB>;
@@ -141,15 +144,19 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, bool direct_only
 // is resident at once; none fits a tensor whose kept values exceed the register files.
 // A shape whose lanes hold enough consecutive output bytes to store them directly (no
 // pass through the LDS tile after the exchange, measured 2 us shorter on the ViT-B
-// activations) is preferred while it leaves at least 1.25 workgroups per compute unit.
+// activations) is preferred while it leaves at least 1.25 workgroups per compute unit, and
+// among those one whose workgroups write whole 128-byte lines of every output row, so that no
+// line is shared with a workgroup on another XCD (HLA of the ViT-B g_y: 43.1 us with 10
+// blocks per wave against 44.8 us with 7).
 template <int N, int KIND>
 hipError_t launch_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
   hipError_t e = hipSuccess;
-#define HOT_TRY_KB(KB, DIRECT) \
-  if (e == hipSuccess && !*done) e = try_onepass<N, KIND, KB>(a, s, sq, DIRECT, done);
-  HOT_TRY_KB(1, true) HOT_TRY_KB(2, true) HOT_TRY_KB(3, true) HOT_TRY_KB(5, true) HOT_TRY_KB(7, true)
-  HOT_TRY_KB(1, false) HOT_TRY_KB(2, false) HOT_TRY_KB(3, false) HOT_TRY_KB(5, false) HOT_TRY_KB(7, false)
-  HOT_TRY_KB(10, false)
+#define HOT_TRY_KB(KB, ROUND) \
+  if (e == hipSuccess && !*done) e = try_onepass<N, KIND, KB>(a, s, sq, ROUND, done);
+  HOT_TRY_KB(1, 0) HOT_TRY_KB(2, 0) HOT_TRY_KB(4, 0) HOT_TRY_KB(8, 0) HOT_TRY_KB(10, 0)
+  HOT_TRY_KB(1, 1) HOT_TRY_KB(2, 1) HOT_TRY_KB(3, 1) HOT_TRY_KB(5, 1) HOT_TRY_KB(7, 1)
+  HOT_TRY_KB(1, 2) HOT_TRY_KB(2, 2) HOT_TRY_KB(3, 2) HOT_TRY_KB(4, 2) HOT_TRY_KB(5, 2) HOT_TRY_KB(7, 2)
+  HOT_TRY_KB(8, 2) HOT_TRY_KB(10, 2)
 #undef HOT_TRY_KB
   return e;
 }

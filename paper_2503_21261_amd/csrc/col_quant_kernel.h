@@ -453,6 +453,14 @@ __device__ __forceinline__ void pack_kept_codes(const float (&v)[kept_vals<N, KI
 // a lane keeps KB * VEC * kept values for the whole kernel plus DEPTH row buffers of one
 // block (the next block's loads in flight under the current block's butterflies when that
 // still fits).
+// Whether the 4 * KB blocks of a workgroup give every output row a whole number of
+// 128-byte lines (the rows' pitch is a multiple of 128 bytes).
+template <int N, int KIND, int KB>
+constexpr bool onepass_whole_lines() {
+  if constexpr (KIND == kKeepGeneric) return false;
+  else return (4 * KB * static_bpb<N, KIND>()) % 128 == 0;
+}
+
 template <int N, int VEC, int KIND, int KB>
 constexpr int onepass_kept_regs() { return KB * VEC * kept_vals<N, KIND>(); }
 template <int N, int VEC, int KIND, int KB>

@@ -17,7 +17,7 @@ import sys
 
 
 def _short(name: str):
-    m = re.search(r"hot::(\w+)(<[^>]*>)?", name)
+    m = re.search(r"hot::(\w+)(<[^>]*>)?", name.replace("(anonymous namespace)::", ""))
     if m:
         return m.group(1) + (m.group(2) or "")
     if "copyBuffer" in name or "direct_copy" in name:
