@@ -671,8 +671,17 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
   constexpr bool kDirect = onepass_direct_store<N, KIND, KB>();
   if constexpr (kDirect) {
     constexpr int BPB = static_bpb<N, KIND>();
+    // all blocks are packed first and stored afterwards, so that the pieces of one output
+    // line reach L2 back to back and leave it as one full line
     auto emit = [&](auto rounding_c) {
       constexpr int ROUNDING = decltype(rounding_c)::value;
+      uint32_t d[KB][VEC][BPB / 4];
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+        for (int vi = 0; vi < VEC; ++vi) pack_kept_codes<N, KIND, ROUNDING>(v[kb][vi], inv, d[kb][vi]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
         const int slot = w * KB + kb;
@@ -680,17 +689,15 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
         if (gb < nblk && col_ok) {
 #pragma unroll
           for (int vi = 0; vi < VEC; ++vi) {
-            uint32_t d[BPB / 4];
-            pack_kept_codes<N, KIND, ROUNDING>(v[kb][vi], inv, d);
             uint8_t* dst = codes + (c0 + vi) * pitch + gb * BPB;
             if constexpr (BPB % 16 == 0) {
 #pragma unroll
               for (int i = 0; i < BPB / 16; ++i)
-                reinterpret_cast<uint4*>(dst)[i] = make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]);
+                reinterpret_cast<uint4*>(dst)[i] = make_uint4(d[kb][vi][4 * i], d[kb][vi][4 * i + 1], d[kb][vi][4 * i + 2], d[kb][vi][4 * i + 3]);
             } else {
 #pragma unroll
               for (int i = 0; i < BPB / 8; ++i)
-                reinterpret_cast<uint2*>(dst)[i] = make_uint2(d[2 * i], d[2 * i + 1]);
+                reinterpret_cast<uint2*>(dst)[i] = make_uint2(d[kb][vi][2 * i], d[kb][vi][2 * i + 1]);
             }
           }
         }
