@@ -650,6 +650,37 @@ def test_config2_split_k(gemm_mode, mode, wait_us):
     check_gw(hot, cfg, gy, x, "cfg2 split-K")
 
 
+def test_split_k_hand_over_sees_fresh_partial_sums(gemm_mode):
+    """Two different inputs alternate through the same workspace, twelve back-to-back steps
+    without a host synchronisation in between: every g_w must equal the one computed without
+    a K split for that input.  A partial sum left in some cache by an earlier launch, or a
+    flag of an earlier launch taken for a fresh one, would show up here."""
+    hot = _hot()
+    L, O, I = 8192, 384, 256          # 6 tiles of 128x128, K of 32 stages: split in 8
+    cfg = hot.Config(block=32, keep=16)
+    data = [make(L, O, I, seed=61), make(L, O, I, seed=62)]
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    acts, want = [], []
+    gemm_mode(1)
+    for x, w, gy in data:
+        act = hot.alloc_act_buffer(cfg, L, I)
+        hot.hot_compress_activation(cfg, x.cuda(), act, ws)
+        gw = torch.empty((O, I), device="cuda")
+        hot.hot_linear_backward_gw(cfg, gy.cuda(), act, I, gw, ws)
+        torch.cuda.synchronize()
+        acts.append(act)
+        want.append(gw.clone())
+    assert not torch.equal(want[0], want[1])
+    gemm_mode(0)
+    gys = [d[2].cuda() for d in data]
+    outs = [torch.empty((O, I), device="cuda") for _ in range(12)]
+    for step in range(12):
+        hot.hot_linear_backward_gw(cfg, gys[step % 2], acts[step % 2], I, outs[step], ws)
+    torch.cuda.synchronize()
+    for step in range(12):
+        assert torch.equal(outs[step], want[step % 2]), f"step {step}"
+
+
 # ---- maximum reduction lengths: accumulators at the edge of int32 ------------------------
 
 def _hadamard_np(n):
