@@ -592,8 +592,12 @@ def test_gx_combined_and_separate_launches_agree():
     bits, with the exchange of the weight workgroups both waited for and skipped."""
     hot = _hot()
     try:
+        # O at both ends of every row-kernel variant the combined launch has (257..4096), token
+        # counts that leave the last 4-row workgroup partly empty, weights of one tile and of
+        # hundreds, and shapes just outside (O = 256, 4160: separate launches either way)
         for (L, O, I, n) in [(2048, 768, 768, 32), (1024, 3072, 768, 32), (788, 512, 1024, 16), (4096, 4096, 256, 64),
-                             (512, 1024, 128, 16)]:
+                             (512, 1024, 128, 16), (1030, 272, 64, 16), (777, 1040, 72, 16), (130, 2048, 66, 32),
+                             (96, 256, 64, 32), (64, 4160, 32, 32)]:
             x, w, gy = make(L, O, I, seed=53)
             cfg = hot.Config(block=n, keep=n // 2)
             outs = []
