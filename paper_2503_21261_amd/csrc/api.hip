@@ -306,27 +306,60 @@ hipError_t gemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_
                       out_i32, out_f32, row_scale, row_stride, col_scale, n, s, stage);
 }
 
-// The g_x path given quantised weights (codes [I x pitch], scale): rotate and quantise
-// g_y, multiply, dequantise.
-hot_status run_gx(const Config& c, const float* g_y, const uint8_t* qw, const float* s_w, int64_t L,
-                  int64_t O, int64_t I, hot_quantizer gy_quantizer, float* g_x, uint8_t* base,
-                  const GxLayout& g, hipStream_t s, bool rows_done = false) {
+// g_x path, first half: the rotated, quantised g_y operand (codes at g.qg, scales at g.sg).
+hot_status gx_rows(const Config& c, const float* g_y, int64_t L, int64_t O, hot_quantizer gy_quantizer,
+                   uint8_t* base, const GxLayout& g, hipStream_t s) {
   float* part_g = (float*)(base + kHeaderBytes + kPartialBytes);
   float* s_g = (float*)(base + g.sg);
   uint8_t* qg = base + g.qg;
   int npart = 0;
-  if (rows_done) {
-    // the quantised g_y is already in place (combined launch with the weights)
-  } else if (gy_quantizer == HOT_Q_PER_TOKEN) {
+  if (gy_quantizer == HOT_Q_PER_TOKEN) {
     HOT_STAGE(kStGyRowQuant, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 0, qg, g.pitch, s_g, part_g, &npart, s));
   } else {
     HOT_STAGE(kStGyRowAbsmax, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 1, qg, g.pitch, s_g, part_g, &npart, s));
     HOT_STAGE(kStGyRowQuant2, launch_row_quant(g_y, L, O, c.n, c.gx_bits, c.rounding, 2, qg, g.pitch, s_g, part_g, &npart, s));
   }
-  HOT_TRY(gemm(qg, qw, L, I, g.pitch, c.gx_bits, base, g.partial, nullptr, g_x, s_g,
-               gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
+
+// g_x path, both operands from fp32 inputs: Q(H.w) as [I x O] code rows with its scale at
+// g.scalars, and gx_rows; in one launch where that exists, else one after the other.
+hot_status gx_operands(const Config& c, const float* g_y, const float* w, int64_t L, int64_t O, int64_t I,
+                       hot_quantizer gy_quantizer, uint8_t* base, const GxLayout& g, hipStream_t s) {
+  float* s_w = (float*)(base + g.scalars);
+  float* part_w = (float*)(base + kHeaderBytes);
+  uint8_t* qw = base + g.qw;
+  bool both = false;
+  if (gy_quantizer == HOT_Q_PER_TOKEN && g_backward_strategy.load() != 3)
+    HOT_TRY(launch_w_and_rows(w, O, I, c, qw, g.pitch, s_w, part_w, g_y, L, base + g.qg,
+                              (float*)(base + g.sg), s, kStWGyRow, &both));
+  if (both) return HOT_OK;
+  HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
+                           part_w, s, kStWAbsmax, kStWQuant));
+  return gx_rows(c, g_y, L, O, gy_quantizer, base, g, s);
+}
+
+// g_x path, second half: multiply the operand at g.qg with quantised weights, dequantise.
+hot_status gx_gemm(const Config& c, const uint8_t* qw, const float* s_w, int64_t L, int64_t I,
+                   hot_quantizer gy_quantizer, float* g_x, uint8_t* base, const GxLayout& g,
+                   hipStream_t s) {
+  HOT_TRY(gemm(base + g.qg, qw, L, I, g.pitch, c.gx_bits, base, g.partial, nullptr, g_x,
+               (const float*)(base + g.sg), gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
+  return HOT_OK;
+}
+
+// HLA(g_y) along L as [O x L'] code rows at `qg` with its scale at `s_g` (INT8: one scale;
+// bfloat16: no scale, 1 is stored), then the GEMM with the stored activation and dequantise.
+hot_status gw_operand(const Config& c, const float* g_y, int64_t L, int64_t O, uint8_t* qg, int64_t pitch,
+                      float* s_g, float* slots, hipStream_t s) {
+  if (c.gw_bits == 16)
+    HOT_TRY(launch_col_bf16(g_y, row_tiling(c, L), O, c, qg, pitch, s_g, s, kStGyTQuant));
+  else
+    HOT_TRY(launch_col_quant(g_y, row_tiling(c, L), O, c, c.r, c.map, false, c.gw_bits, qg, pitch, s_g, slots, s,
+                             kStGyTAbsmax, kStGyTQuant));
+  return HOT_OK;
+}
+
 
 }  // namespace
 
@@ -344,19 +377,9 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   if (ws_bytes < g.total) return HOT_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
-  float* s_w = (float*)(base + g.scalars);
-  float* part_w = (float*)(base + kHeaderBytes);
-  uint8_t* qw = base + g.qw;
-  // H.w along O, one scale, written as [I x O] code rows: together with the per-token
-  // g_y operand in one launch where that exists, else on its own
-  bool both = false;
-  if (gy_quantizer == HOT_Q_PER_TOKEN && g_backward_strategy.load() != 3)
-    HOT_TRY(launch_w_and_rows(w, O, I, c, qw, g.pitch, s_w, part_w, g_y, L, base + g.qg,
-                              (float*)(base + g.sg), s, kStWGyRow, &both));
-  if (!both)
-    HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, qw, g.pitch, s_w,
-                             part_w, s, kStWAbsmax, kStWQuant));
-  return run_gx(c, g_y, qw, s_w, L, O, I, gy_quantizer, g_x, base, g, s, both);
+  st = gx_operands(c, g_y, w, L, O, I, gy_quantizer, base, g, s);
+  if (st != HOT_OK) return st;
+  return gx_gemm(c, base + g.qw, (const float*)(base + g.scalars), L, I, gy_quantizer, g_x, base, g, s);
 }
 
 hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
@@ -375,8 +398,9 @@ hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y
   if (ws_bytes < g.qw) return HOT_ERR_WORKSPACE;   // the weight-code region of ws is not needed
   const WeightLayout wl = weight_layout(c, O, I);
   const uint8_t* wb = (const uint8_t*)wq_buf;
-  return run_gx(c, g_y, wb + wl.codes, (const float*)wb, L, O, I, gy_quantizer, g_x, (uint8_t*)ws, g,
-                (hipStream_t)stream);
+  st = gx_rows(c, g_y, L, O, gy_quantizer, (uint8_t*)ws, g, (hipStream_t)stream);
+  if (st != HOT_OK) return st;
+  return gx_gemm(c, wb + wl.codes, (const float*)wb, L, I, gy_quantizer, g_x, (uint8_t*)ws, g, (hipStream_t)stream);
 }
 
 hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
@@ -399,12 +423,8 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   uint8_t* qg = base + g.qg;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
-  // HLA(g_y) along L, one scale, written as [O x L'] code rows
-  if (c.gw_bits == 16)
-    HOT_TRY(launch_col_bf16(g_y, row_tiling(c, L), O, c, qg, g.pitch, s_g, s, kStGyTQuant));
-  else
-    HOT_TRY(launch_col_quant(g_y, row_tiling(c, L), O, c, c.r, c.map, false, c.gw_bits, qg, g.pitch, s_g, part_g, s,
-                             kStGyTAbsmax, kStGyTQuant));
+  st = gw_operand(c, g_y, L, O, qg, g.pitch, s_g, part_g, s);
+  if (st != HOT_OK) return st;
   HOT_TRY(gemm(qg, abase + a.codes, O, I, g.pitch, c.gw_bits, base, g.partial, nullptr, g_w, s_g, 0,
                (const float*)abase, c.n, s, kStGwGemm));
   return HOT_OK;
@@ -422,16 +442,16 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
+  const FusedLayout f = fused_layout(c, L, O, I);
+  const ActLayout a = act_layout(c, L, I);
+  hipStream_t s = (hipStream_t)stream;
+  uint8_t* base = (uint8_t*)ws;
   if (!shared_gy_passes(c, L, O)) {
     st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
     if (st != HOT_OK) return st;
     return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
   }
-  const FusedLayout f = fused_layout(c, L, O, I);
   if (ws_bytes < f.total) return HOT_ERR_WORKSPACE;
-  const ActLayout a = act_layout(c, L, I);
-  hipStream_t s = (hipStream_t)stream;
-  uint8_t* base = (uint8_t*)ws;
   float* s_w = (float*)(base + f.gx.scalars);
   float* s_gh = (float*)(base + f.s_gh);
   float* part_a = (float*)(base + kHeaderBytes);
