@@ -127,24 +127,23 @@ __device__ __forceinline__ void store_block_codes(const float (&v)[VEC][N], uint
     } else if constexpr (KIND == kKeepAll4) {
 #pragma unroll
       for (int k8 = 0; k8 < N / 8; ++k8) {
-        uint32_t d = 0;
+        int c[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-          d |= (uint32_t)(quant_code(v[vi][k8 * 8 + e], inv, QMAX, rounding) & 0xF) << (4 * e);
-        reinterpret_cast<uint32_t*>(dst)[k8] = d;
+        for (int e = 0; e < 8; ++e) c[e] = quant_code(v[vi][k8 * 8 + e], inv, QMAX, rounding);
+        reinterpret_cast<uint32_t*>(dst)[k8] = pack8_codes4(c);
       }
     } else {
       constexpr int RK = KIND == kKeepLowHalf ? N / 2 : N;
 #pragma unroll
       for (int j4 = 0; j4 < RK / 4; ++j4) {
-        uint32_t d = 0;
+        int c[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = j4 * 4 + e;
           const int k = KIND == kKeepLowHalf ? lowpass_row(N, j) : j;
-          d |= (uint32_t)(quant_code(v[vi][k], inv, QMAX, rounding) & 0xFF) << (8 * e);
+          c[e] = quant_code(v[vi][k], inv, QMAX, rounding);
         }
-        reinterpret_cast<uint32_t*>(dst)[j4] = d;
+        reinterpret_cast<uint32_t*>(dst)[j4] = pack4_codes8(c[0], c[1], c[2], c[3]);
       }
     }
   }
@@ -300,13 +299,10 @@ __device__ __forceinline__ void store_kept_form_codes(const float (&v)[VEC][kept
       uint32_t* dst = reinterpret_cast<uint32_t*>(tile + (vi * 64 + lane) * TBP + off);
 #pragma unroll
       for (int j4 = 0; j4 < N / 8; ++j4) {
-        uint32_t d = 0;
+        int c[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int k = lowpass_row(N, j4 * 4 + e) >> 1;
-          d |= (uint32_t)(quant_code(v[vi][k], inv, 127, rounding) & 0xFF) << (8 * e);
-        }
-        dst[j4] = d;
+        for (int e = 0; e < 4; ++e) c[e] = quant_code(v[vi][lowpass_row(N, j4 * 4 + e) >> 1], inv, 127, rounding);
+        dst[j4] = pack4_codes8(c[0], c[1], c[2], c[3]);
       }
     }
   } else {
@@ -429,22 +425,21 @@ __device__ __forceinline__ void pack_kept_codes(const float (&v)[kept_vals<N, KI
   if constexpr (KIND == kKeepAll4) {
 #pragma unroll
     for (int k8 = 0; k8 < N / 8; ++k8) {
-      uint32_t d = 0;
+      int c[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d |= (uint32_t)(quant_code(v[k8 * 8 + e], inv, 7, ROUNDING) & 0xF) << (4 * e);
-      out[k8] = d;
+      for (int e = 0; e < 8; ++e) c[e] = quant_code(v[k8 * 8 + e], inv, 7, ROUNDING);
+      out[k8] = pack8_codes4(c);
     }
   } else {
 #pragma unroll
     for (int j4 = 0; j4 < static_bpb<N, KIND>() / 4; ++j4) {
-      uint32_t d = 0;
+      int c[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int j = j4 * 4 + e;
-        const int k = KIND == kKeepLowHalf ? (lowpass_row(N, j) >> 1) : j;
-        d |= (uint32_t)(quant_code(v[k], inv, 127, ROUNDING) & 0xFF) << (8 * e);
+        c[e] = quant_code(v[KIND == kKeepLowHalf ? (lowpass_row(N, j) >> 1) : j], inv, 127, ROUNDING);
       }
-      out[j4] = d;
+      out[j4] = pack4_codes8(c[0], c[1], c[2], c[3]);
     }
   }
 }

@@ -221,13 +221,11 @@ __global__ __launch_bounds__(256) void gy_fused_quant_kernel(
         uint32_t* dst = reinterpret_cast<uint32_t*>(tile + (vi * 64 + lane) * TBP + slot * bpb);
 #pragma unroll
         for (int j4 = 0; j4 < N / 8; ++j4) {
-          uint32_t d = 0;
+          int q[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int k = lowpass_row(N, j4 * 4 + e) >> 1;   // even natural row 2k' sits at c[k']
-            d |= (uint32_t)(quant_code(c[vi][k], inv_h, 127, rounding) & 0xFF) << (8 * e);
-          }
-          dst[j4] = d;
+          for (int e = 0; e < 4; ++e)   // even natural row 2k' sits at c[k']
+            q[e] = quant_code(c[vi][lowpass_row(N, j4 * 4 + e) >> 1], inv_h, 127, rounding);
+          dst[j4] = pack4_codes8(q[0], q[1], q[2], q[3]);
         }
       }
     } else {

@@ -119,6 +119,22 @@ __device__ __forceinline__ int quant_code(float t, float inv, int qmax, int roun
   return min(max(q, -qmax), qmax);
 }
 
+// Four int8 codes (the low byte of each int) as one dword, c0 in byte 0: three byte
+// permutes instead of a mask, a shift and an or per code.
+__device__ __forceinline__ uint32_t pack4_codes8(int c0, int c1, int c2, int c3) {
+  const uint32_t lo = __builtin_amdgcn_perm((uint32_t)c1, (uint32_t)c0, 0x0c0c0400u);
+  const uint32_t hi = __builtin_amdgcn_perm((uint32_t)c3, (uint32_t)c2, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// Eight int4 codes (the low nibble of each int) as one dword, c[0] in the lowest nibble.
+__device__ __forceinline__ uint32_t pack8_codes4(const int (&c)[8]) {
+  int b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = (c[2 * i] & 0xF) | (c[2 * i + 1] << 4);   // byte 0 is what counts
+  return pack4_codes8(b[0], b[1], b[2], b[3]);
+}
+
 // Maximum of partials[0..count), returned to every thread of a 256-thread workgroup.
 // The abs-max kernels leave one partial per workgroup; their consumers call this
 // first, so no atomics and no pre-zeroed memory are involved.

@@ -21,8 +21,7 @@ __device__ __forceinline__ void store_codes4(uint8_t* row_codes, int e, const fl
     const unsigned p = (c0 & 0xF) | ((c1 & 0xF) << 4) | ((c2 & 0xF) << 8) | ((c3 & 0xF) << 12);
     *reinterpret_cast<uint16_t*>(row_codes + (e >> 1)) = (uint16_t)p;
   } else {
-    const unsigned p = (c0 & 0xFF) | ((c1 & 0xFF) << 8) | ((c2 & 0xFF) << 16) | ((unsigned)(c3 & 0xFF) << 24);
-    *reinterpret_cast<uint32_t*>(row_codes + e) = p;
+    *reinterpret_cast<uint32_t*>(row_codes + e) = pack4_codes8(c0, c1, c2, c3);
   }
 }
 
