@@ -23,6 +23,10 @@
  *     launch, so a failing call has launched nothing.  Inputs must be finite.
  *   - Two calls that share a workspace or an output must be ordered by the
  *     caller (same stream, or events).
+ *   - Calls must not be recorded into a HIP graph: the kernels whose workgroups
+ *     exchange values through the workspace (single-pass transforms, split-K
+ *     GEMM) tell a launch's values from stale ones by a tag chosen on the host
+ *     per call, and a replayed graph would repeat it.
  */
 #ifndef HOT_H
 #define HOT_H
