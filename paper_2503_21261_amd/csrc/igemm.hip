@@ -44,7 +44,7 @@ hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t 
 // workgroups per compute unit, so one workgroup's stores overlap the others' main
 // loops, but the INT4 widening costs 6 vector instructions per matrix instruction and
 // the vector pipe becomes the limit; with INT8 operands its LDS traffic, 1 KB per matrix
-// instruction, is the limit), 192x256 and 256x256 (96x128 / 128x128 per wave, one workgroup
+// instruction, is the limit), 192x256 and 256x256 (96x128 / 128x128 per wave, 64x128 for INT8; one workgroup
 // per unit, half the widening and LDS traffic per matrix instruction, but nothing hides the
 // output stores and a partial last round idles units).  The choice minimises a cost model
 // fitted to measurements on MI355X: rounds over the compute units x (tile operations /
@@ -85,7 +85,7 @@ void set_gemm_wait_us(int us) { g_gemm_wait_us.store(us); }
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch) {
   struct Cand { int bm, bn; double tops; bool hides_stores; };
   static const Cand cands4[] = {{128, 128, 1900., true}, {192, 256, 2700., false}, {256, 256, 3200., false}};
-  static const Cand cands8[] = {{128, 128, 1000., true}, {256, 256, 2200., false}};
+  static const Cand cands8[] = {{128, 128, 1000., true}, {256, 256, 2550., false}};
   const Cand* cands = bits == 4 ? cands4 : cands8;
   const int ncand = bits == 4 ? 3 : 2;
   const double K = (double)k_bytes * (bits == 4 ? 2 : 1);
@@ -139,10 +139,20 @@ uint32_t next_gemm_tag() {
   return tag.fetch_add(1, std::memory_order_relaxed);
 }
 
+// Waves per workgroup: 2x2, except 4x2 for the 256x256 INT8 tile.  Its four waves, alone on
+// their SIMDs, cannot hide the LDS traffic of INT8 operands (twice the bytes per matrix
+// instruction of packed INT4); eight waves of 64x128 each, two per SIMD, keep the whole
+// accumulator tile in the 512 registers per lane all the same.  Measured on the LLM-sized g_w
+// GEMM: 320 us against 364 us (4x4 waves: 351 us; the INT4 tile and the 128x128 INT8 tile do
+// not gain from more waves).
+template <int BM, bool INT4, bool BF16>
+constexpr int gemm_waves_m() { return (BM == 256 && !INT4 && !BF16) ? 4 : 2; }
+
 template <int BM, int BN, int BKB, bool INT4, bool BF16, bool SPLITK>
 hipError_t launch_kernel(const GemmArgs& g, unsigned grid, hipStream_t s, int gemm_stage) {
   const size_t lds = 2 * (size_t)(BM + BN) * BKB;
-  auto kern = igemm_kernel<BM, BN, 2, 2, BKB, INT4, BF16, SPLITK>;
+  constexpr int WM = gemm_waves_m<BM, INT4, BF16>();
+  auto kern = igemm_kernel<BM, BN, WM, 2, BKB, INT4, BF16, SPLITK>;
   static std::atomic<bool> attr_set{false};  // per instantiation; setting it twice is harmless
   if (!attr_set.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -150,7 +160,7 @@ hipError_t launch_kernel(const GemmArgs& g, unsigned grid, hipStream_t s, int ge
     attr_set.store(true, std::memory_order_release);
   }
   if (gemm_stage >= 0) stage_begin(gemm_stage, s);
-  kern<<<dim3(grid), dim3(256), lds, s>>>(g);
+  kern<<<dim3(grid), dim3(64 * WM * 2), lds, s>>>(g);
   if (gemm_stage >= 0) stage_end(gemm_stage, s);
   return hipGetLastError();
 }

@@ -81,8 +81,9 @@ __device__ __forceinline__ void tile_of_position(const GemmArgs& g, int id, int&
 }
 
 // ---- main loop ---------------------------------------------------------------------
-// One wave per SIMD at the large tile (the accumulators of a 128x128 wave tile fill
-// the AGPRs), so latency is hidden inside the wave rather than by occupancy:
+// One wave per SIMD at the large INT4 tile (the accumulators of a 128x128 wave tile fill
+// the AGPRs), two at the large INT8 tile (eight waves of 64x128), so latency is hidden inside
+// the wave rather than by occupancy:
 //   - global loads run two K stages ahead (registers), LDS holds two stages;
 //   - the 16-byte LDS fragments of K slice ks+1 are read, and (INT4) widened, while
 //     the matrix instructions of slice ks execute;
