@@ -115,7 +115,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch
     // measured on MI355X (128x128 INT8 tiles, K of 50-200 stages): fastest with as many slices
     // as keep all workgroups resident at once, two per compute unit; a partial second round
     // costs more than the shorter slices gain
-    int64_t s = mode >= 2 ? mode : (p.tiles < cus ? 2 * cus / p.tiles : 1);
+    int64_t s = mode >= 2 ? mode : (p.tiles <= cus ? 2 * cus / p.tiles : 1);
     if (s > most) s = most;
     if (s >= 2) {
       p.split = (int)s;
