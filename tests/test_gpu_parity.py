@@ -654,6 +654,18 @@ def test_config2_split_k(gemm_mode, mode, wait_us):
     check_gw(hot, cfg, gy, x, "cfg2 split-K")
 
 
+def test_int8_gemm_on_the_large_tile():
+    """Shapes for which the INT8 GEMMs take the 256x256 tile (eight waves per workgroup), with
+    ragged edges in both directions: the g_w GEMM of a 2200 x 2100 weight and the INT8 g_x
+    GEMM of 4000 tokens; every accumulator is compared."""
+    hot = _hot()
+    x, w, gy = make(8192, 2200, 2100, seed=71)     # K = 4096 bytes: long enough for the planner
+    check_gw(hot, hot.Config(block=16, keep=8), gy, x, "large INT8 tile, g_w")
+    x, w, gy = make(4000, 8192, 1100, seed=72)
+    check_gx(hot, hot.Config(block=16, keep=8, gx_bits=8), gy, w, False, "large INT8 tile, g_x")
+    check_gx(hot, hot.Config(block=16, keep=8, gx_bits=8), gy, w, True, "large INT8 tile, g_x")
+
+
 def test_split_k_hand_over_sees_fresh_partial_sums(gemm_mode):
     """Two different inputs alternate through the same workspace, twelve back-to-back steps
     without a host synchronisation in between: every g_w must equal the one computed without
