@@ -77,6 +77,21 @@ int64_t max_split(int64_t tiles, int64_t nk) {
   while (s > 1 && tiles * (s - 1) > kMaxSplitSlots) --s;
   return s < 1 ? 1 : s;
 }
+// K split of the 256x256 INT8 tile (eight waves, one workgroup per compute unit) for an output
+// of at most one such tile per unit: as many slices as there are units per tile, and only when
+// a slice keeps at least 16 KB of K, so that the 256 KB accumulator images the owner collects
+// are a small part of the work.  Measured: ViT-L fc1 g_w (64 tiles, K = 100864, 4 slices) 396 us
+// against 483 us with 128x128 tiles in 2 slices; with 3152-byte slices (ViT-B qkv) 88 against
+// 79 us, so short K stays on the small tile.  0: does not apply.
+int64_t large_tile_split(int64_t M, int64_t N, int64_t k_bytes, int bits, int cus) {
+  if (bits != 8) return 0;
+  const int64_t tiles = ceil_div(M, 256) * ceil_div(N, 256);
+  if (tiles > cus) return 0;
+  int64_t s = cus / tiles;
+  if (s > 8) s = 8;
+  while (s > 1 && (k_bytes / s < 16384 || tiles * (s - 1) > kMaxSplitSlots)) --s;
+  return s >= 2 ? s : 0;
+}
 }  // namespace
 
 void set_gemm_mode(int mode) { g_gemm_mode.store(mode); }
@@ -110,6 +125,16 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch
   }
   p.bkb = bits == 4 ? 64 : 128;
   const int mode = g_gemm_mode.load();
+  if (scratch && mode == 0) {
+    const int64_t s = large_tile_split(M, N, k_bytes, bits, cus);
+    if (s) {
+      p.bm = p.bn = 256;
+      p.tiles = ceil_div(M, 256) * ceil_div(N, 256);
+      p.split = (int)s;
+      p.partial_bytes = (size_t)p.tiles * (s - 1) * 256 * 256 * 4;
+      return p;
+    }
+  }
   if (scratch && bits != 16 && p.bm == 128 && mode != 1) {
     const int64_t nk = k_bytes / p.bkb, most = max_split(p.tiles, nk);
     // measured on MI355X (128x128 INT8 tiles, K of 50-200 stages): fastest with as many slices
@@ -129,7 +154,10 @@ size_t gemm_scratch_bytes(int64_t M, int64_t N, int64_t k_bytes, int bits) {
   if (bits == 16 || M <= 0 || N <= 0) return 0;
   const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
   const int64_t s = max_split(tiles, k_bytes / (bits == 4 ? 64 : 128));
-  return (size_t)tiles * (s - 1) * 128 * 128 * 4;
+  const size_t small = (size_t)tiles * (s - 1) * 128 * 128 * 4;
+  const int64_t sl = large_tile_split(M, N, k_bytes, bits, compute_units());
+  const size_t large = sl ? (size_t)(ceil_div(M, 256) * ceil_div(N, 256)) * (sl - 1) * 256 * 256 * 4 : 0;
+  return small > large ? small : large;
 }
 
 namespace {
@@ -173,8 +201,8 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, in
   g.split = split;
   const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
   if (split <= 1) return launch_kernel<BM, BN, BKB, INT4, BF16, false>(g, (unsigned)tiles, s, gemm_stage);
-  if constexpr (BF16 || BM != 128) {
-    return hipErrorInvalidValue;   // only the small tile is ever split
+  if constexpr (BF16 || BM == 192 || (INT4 && BM != 128)) {
+    return hipErrorInvalidValue;   // splits exist for the 128x128 tiles and the 256x256 INT8 tile
   } else {
     if (!g.partial || !g.flags || tiles * (split - 1) > kMaxSplitSlots) return hipErrorInvalidValue;
     g.tag = next_gemm_tag();

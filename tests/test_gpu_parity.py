@@ -666,6 +666,16 @@ def test_int8_gemm_on_the_large_tile():
     check_gx(hot, hot.Config(block=16, keep=8, gx_bits=8), gy, w, True, "large INT8 tile, g_x")
 
 
+@pytest.mark.parametrize("wait_us", [200, 0])
+def test_int8_gemm_large_tile_with_k_split(gemm_mode, wait_us):
+    """A small output with a very long K (40000 reduced tokens): the g_w GEMM takes the 256x256
+    tile with K in two slices; with wait 0 the owner computes the other slice itself."""
+    hot = _hot()
+    hot.hot_debug_set_exchange_wait_us(wait_us)
+    x, w, gy = make(80000, 300, 260, seed=73)
+    check_gw(hot, hot.Config(block=16, keep=8), gy, x, f"large INT8 tile, K split, wait={wait_us}")
+
+
 def test_split_k_hand_over_sees_fresh_partial_sums(gemm_mode):
     """Two different inputs alternate through the same workspace, twelve back-to-back steps
     without a host synchronisation in between: every g_w must equal the one computed without
