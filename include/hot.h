@@ -225,9 +225,10 @@ hot_status hot_debug_set_backward_strategy(int strategy);
  * to a split-K GEMM's wait for another workgroup's partial sums.  Process-wide setting. */
 hot_status hot_debug_set_exchange_wait_us(int us);
 
-/* Work distribution of the GEMMs: 0 = chosen by the library (default), 1 = one workgroup
- * per output tile, s = 2..8: the K range cut into s slices, one workgroup each, wherever a
- * split applies (integer operands, small tile, at least 4 K stages per slice); the slices'
+/* Work distribution of the GEMMs: 0 = chosen by the library (default: K is split for
+ * outputs with no more tiles than compute units), 1 = one workgroup per output tile,
+ * s = 2..8: the K range cut into s slices, one workgroup each, wherever a split of the
+ * 128x128 tile applies (integer operands, at least 4 K stages per slice); the slices'
  * partial sums are handed to the last one through the workspace.  Integer results, and
  * therefore all outputs, do not depend on it.  Process-wide. */
 hot_status hot_debug_set_gemm_mode(int mode);
