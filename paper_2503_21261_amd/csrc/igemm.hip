@@ -167,14 +167,14 @@ uint32_t next_gemm_tag() {
   return tag.fetch_add(1, std::memory_order_relaxed);
 }
 
-// Waves per workgroup: 2x2, except 4x2 for the 256x256 INT8 tile.  Its four waves, alone on
-// their SIMDs, cannot hide the LDS traffic of INT8 operands (twice the bytes per matrix
-// instruction of packed INT4); eight waves of 64x128 each, two per SIMD, keep the whole
-// accumulator tile in the 512 registers per lane all the same.  Measured on the LLM-sized g_w
-// GEMM: 320 us against 364 us (4x4 waves: 351 us; the INT4 tile and the 128x128 INT8 tile do
-// not gain from more waves).
+// Waves per workgroup: 2x2, except 4x2 for the 256x256 INT8 and bfloat16 tiles.  Four waves,
+// alone on their SIMDs, cannot hide the LDS traffic of those operands (two and four times the
+// bytes per matrix instruction of packed INT4); eight waves of 64x128 each, two per SIMD, keep
+// the whole accumulator tile in the 512 registers per lane all the same.  Measured on the
+// LLM-sized g_w GEMM: INT8 320 us against 364 us (4x4 waves: 351 us), bfloat16 640 against
+// 688 us; the INT4 tile and the 128x128 tiles do not gain from more waves.
 template <int BM, bool INT4, bool BF16>
-constexpr int gemm_waves_m() { return (BM == 256 && !INT4 && !BF16) ? 4 : 2; }
+constexpr int gemm_waves_m() { return (BM == 256 && !INT4) ? 4 : 2; }
 
 template <int BM, int BN, int BKB, bool INT4, bool BF16, bool SPLITK>
 hipError_t launch_kernel(const GemmArgs& g, unsigned grid, hipStream_t s, int gemm_stage) {
