@@ -666,6 +666,13 @@ def test_int8_gemm_on_the_large_tile():
     check_gx(hot, hot.Config(block=16, keep=8, gx_bits=8), gy, w, True, "large INT8 tile, g_x")
 
 
+def test_bf16_gemm_on_the_large_tile():
+    """The bfloat16 g_w GEMM of a 2200 x 2100 weight takes the 256x256 tile (eight waves)."""
+    hot = _hot()
+    x, w, gy = make(8192, 2200, 2100, seed=74)
+    check_gw_bf16(hot, hot.Config(block=16, keep=8, gw_bits=16), gy, x, "large bf16 tile")
+
+
 @pytest.mark.parametrize("wait_us", [200, 0])
 def test_int8_gemm_large_tile_with_k_split(gemm_mode, wait_us):
     """A small output with a very long K (40000 reduced tokens): the g_w GEMM takes the 256x256
