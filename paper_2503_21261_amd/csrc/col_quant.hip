@@ -123,6 +123,10 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, int round, bool*
     }
     if (tiles > (int64_t)per_cu * cus || tiles > kMaxPartials / 2) return hipSuccess;
     if (direct_only && tiles * 4 < 5 * (int64_t)cus) return hipSuccess;
+    // ... and at most two: with three or more per compute unit both the read and the final
+    // stores measured slower (155 MB of 16-row blocks: 48.7 us on 678 workgroups of 7 blocks
+    // per wave against 41.1 us on 474 of 10)
+    if (direct_only && tiles > 2 * (int64_t)cus) return hipSuccess;
     // the other workgroups need at least the time to stream their share of the input:
     // never wait less than the whole tensor takes at 1 TB/s (0 stays 0: tests force the
     // self-computed path with it)
@@ -144,7 +148,7 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, int round, bool*
 // is resident at once; none fits a tensor whose kept values exceed the register files.
 // A shape whose lanes hold enough consecutive output bytes to store them directly (no
 // pass through the LDS tile after the exchange, measured 2 us shorter on the ViT-B
-// activations) is preferred while it leaves at least 1.25 workgroups per compute unit, and
+// activations) is preferred while it leaves between 1.25 and 2 workgroups per compute unit, and
 // among those one whose workgroups write whole 128-byte lines of every output row, so that no
 // line is shared with a workgroup on another XCD (HLA of the ViT-B g_y: 43.1 us with 10
 // blocks per wave against 44.8 us with 7).
@@ -154,7 +158,8 @@ hipError_t launch_onepass(const ColArgs& a, hipStream_t s, int sq, bool* done) {
 #define HOT_TRY_KB(KB, ROUND) \
   if (e == hipSuccess && !*done) e = try_onepass<N, KIND, KB>(a, s, sq, ROUND, done);
   HOT_TRY_KB(1, 0) HOT_TRY_KB(2, 0) HOT_TRY_KB(4, 0) HOT_TRY_KB(8, 0) HOT_TRY_KB(10, 0)
-  HOT_TRY_KB(1, 1) HOT_TRY_KB(2, 1) HOT_TRY_KB(3, 1) HOT_TRY_KB(5, 1) HOT_TRY_KB(7, 1)
+  HOT_TRY_KB(1, 1) HOT_TRY_KB(2, 1) HOT_TRY_KB(3, 1) HOT_TRY_KB(4, 1) HOT_TRY_KB(5, 1) HOT_TRY_KB(7, 1)
+  HOT_TRY_KB(8, 1) HOT_TRY_KB(10, 1)
   HOT_TRY_KB(1, 2) HOT_TRY_KB(2, 2) HOT_TRY_KB(3, 2) HOT_TRY_KB(4, 2) HOT_TRY_KB(5, 2) HOT_TRY_KB(7, 2)
   HOT_TRY_KB(8, 2) HOT_TRY_KB(10, 2)
 #undef HOT_TRY_KB

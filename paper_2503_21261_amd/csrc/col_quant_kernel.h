@@ -677,22 +677,38 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
         for (int vi = 0; vi < VEC; ++vi) pack_kept_codes<N, KIND, ROUNDING>(v[kb][vi], inv, d[kb][vi]);
       }
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (BPB == 8 && KB % 2 == 0) {
+        // 8-byte blocks: two consecutive blocks make one aligned 16-byte store (a wave's
+        // first block is even; a partner block past the end holds zero codes, which is what
+        // the padding up to the pitch holds anyway)
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-        const int slot = w * KB + kb;
-        const int64_t gb = ty * 4 * KB + slot;
-        if (gb < nblk && col_ok) {
+        for (int kb = 0; kb < KB; kb += 2) {
+          const int64_t gb = ty * 4 * KB + w * KB + kb;
+          if (gb < nblk && col_ok) {
 #pragma unroll
-          for (int vi = 0; vi < VEC; ++vi) {
-            uint8_t* dst = codes + (c0 + vi) * pitch + gb * BPB;
-            if constexpr (BPB % 16 == 0) {
+            for (int vi = 0; vi < VEC; ++vi)
+              *reinterpret_cast<uint4*>(codes + (c0 + vi) * pitch + gb * BPB) =
+                  make_uint4(d[kb][vi][0], d[kb][vi][1], d[kb + 1][vi][0], d[kb + 1][vi][1]);
+          }
+        }
+      } else {
 #pragma unroll
-              for (int i = 0; i < BPB / 16; ++i)
-                reinterpret_cast<uint4*>(dst)[i] = make_uint4(d[kb][vi][4 * i], d[kb][vi][4 * i + 1], d[kb][vi][4 * i + 2], d[kb][vi][4 * i + 3]);
-            } else {
+        for (int kb = 0; kb < KB; ++kb) {
+          const int slot = w * KB + kb;
+          const int64_t gb = ty * 4 * KB + slot;
+          if (gb < nblk && col_ok) {
 #pragma unroll
-              for (int i = 0; i < BPB / 8; ++i)
-                reinterpret_cast<uint2*>(dst)[i] = make_uint2(d[kb][vi][2 * i], d[kb][vi][2 * i + 1]);
+            for (int vi = 0; vi < VEC; ++vi) {
+              uint8_t* dst = codes + (c0 + vi) * pitch + gb * BPB;
+              if constexpr (BPB % 16 == 0) {
+#pragma unroll
+                for (int i = 0; i < BPB / 16; ++i)
+                  reinterpret_cast<uint4*>(dst)[i] = make_uint4(d[kb][vi][4 * i], d[kb][vi][4 * i + 1], d[kb][vi][4 * i + 2], d[kb][vi][4 * i + 3]);
+              } else {
+#pragma unroll
+                for (int i = 0; i < BPB / 8; ++i)
+                  reinterpret_cast<uint2*>(dst)[i] = make_uint2(d[kb][vi][2 * i], d[kb][vi][2 * i + 1]);
+              }
             }
           }
         }
