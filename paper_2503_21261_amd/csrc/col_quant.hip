@@ -32,16 +32,19 @@ ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_d
   else if (lowpass_default && r * 2 == n) p.kind = kKeepLowHalf;
   else p.kind = kKeepGeneric;
   const int bpb = bits == 4 ? n / 2 : r;
-  const int vmax = n == 64 ? 2 : 4;  // at most 128 block values per lane stay in registers
   const int vdiv = (C % 4 == 0) ? 4 : (C % 2 == 0 ? 2 : 1);
   auto tiles = [&](int vec, int kbw) { return ceil_div(C, 64 * vec) * ceil_div(nblk, 4 * kbw); };
-  // Abs-max pass: read-only, so the widest loads win; shrink the tile only while the
-  // 256 compute units would otherwise be short of workgroups.
-  p.vec_a = vdiv < vmax ? vdiv : vmax;
-  p.kbw_a = 2;
-  while (tiles(p.vec_a, p.kbw_a) < 1024 && p.kbw_a > 1) p.kbw_a /= 2;
-  while (tiles(p.vec_a, p.kbw_a) < 512 && p.vec_a > 1) p.vec_a /= 2;
-  const int64_t ta = tiles(p.vec_a, p.kbw_a);
+  // Abs-max pass (a workgroup tile is 256 * vec columns x kbw blocks): about 64 rows per
+  // wave and visit, two or four columns per lane; smaller tiles while the 256 compute units
+  // would otherwise be short of workgroups, narrower ones for narrow tensors.
+  auto tiles_a = [&](int vec, int kbw) { return ceil_div(C, 256 * vec) * ceil_div(nblk, kbw); };
+  const int vpref = n == 16 ? 4 : 2;
+  p.vec_a = vdiv < vpref ? vdiv : vpref;
+  while (p.vec_a > 1 && C < 256 * p.vec_a) p.vec_a /= 2;
+  p.kbw_a = n >= 64 ? 1 : 64 / n;
+  while (tiles_a(p.vec_a, p.kbw_a) < 1024 && p.kbw_a > 1) p.kbw_a /= 2;
+  while (tiles_a(p.vec_a, p.kbw_a) < 512 && p.vec_a > 1) p.vec_a /= 2;
+  const int64_t ta = tiles_a(p.vec_a, p.kbw_a);
   p.absmax_grid = (int)(ta < kMaxPartials ? ta : kMaxPartials);
   // Quantise pass: measured fastest with one column per lane (few registers, many
   // waves) and enough blocks per wave for 256-byte output runs per column.

@@ -323,6 +323,12 @@ __device__ __forceinline__ float workgroup_max(float m) {
 
 // Abs-max pass.  Tiles of (4*kbw blocks) x (64*VEC columns) are dealt to a capped
 // grid; partials[blockIdx.x] = the workgroup's maximum over its tiles.
+// Abs-max pass.  The four waves of a workgroup take adjacent column stripes of the same
+// blocks, so a row of the workgroup's tile is 4 * 64 * VEC consecutive floats requested at
+// about the same time (longer runs per DRAM page than four waves on four different row
+// blocks: 6.0 against 5.3 TB/s on a 721 MB tensor when the kernel runs alone, 152 against
+// 157 us between the GEMMs of a training step); a wave goes through `kbw` consecutive
+// blocks, workgroups loop over the tiles.
 template <int N, int VEC, int KIND>
 __global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict__ x, RowTiling rt,
                                                          int64_t C, KeepMap map, int kbw,
@@ -331,15 +337,15 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(const float* __restrict
   __shared__ float s_max[4];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int64_t nblk = rt.nblk;
-  const int64_t tiles_x = (C + CT - 1) / CT;
-  const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
+  const int64_t tiles_x = (C + 4 * CT - 1) / (4 * CT);
+  const int64_t tiles_y = (nblk + kbw - 1) / kbw;
   float m = 0.0f;
   for (int64_t t = blockIdx.x; t < tiles_x * tiles_y; t += gridDim.x) {
     const int64_t tx = t % tiles_x, ty = t / tiles_x;
-    const int64_t c0 = tx * CT + lane * VEC;
+    const int64_t c0 = tx * 4 * CT + w * CT + lane * VEC;
     if (c0 >= C) continue;
     for (int kb = 0; kb < kbw; ++kb) {
-      const int64_t gb = ty * 4 * kbw + w * kbw + kb;
+      const int64_t gb = ty * kbw + kb;
       if (gb >= nblk) break;
       float v[VEC][kept_vals<N, KIND>()];
       int64_t first;
