@@ -574,6 +574,16 @@ def test_column_quantiser_paths(exchange_wait, wait_us):
             check_gx(hot, hot.Config(block=n, keep=r, keep_idx=keep_idx, gx_bits=8), gy, w, False, f"wait={wait_us}")
 
 
+def test_single_pass_16_row_blocks_with_an_odd_block_count():
+    """16-row blocks leave 8 code bytes per block and column, which the single-pass kernel
+    stores two blocks at a time; with an odd number of blocks the last pair's second half is
+    the row's zero padding (checked through the GEMM, which reads the padding as K)."""
+    hot = _hot()
+    L, O, I = 16 * 3151, 48, 768
+    x, w, gy = make(L, O, I, seed=43)
+    check_gw(hot, hot.Config(block=16, keep=8), gy, x, "odd block count")
+
+
 def test_config2_two_pass_column_kernels(exchange_wait):
     """configs[1] with the single-pass kernels switched off (x and w then take the same
     two-pass kernels as tensors too large for the register files)."""
