@@ -876,3 +876,43 @@ def test_per_sample_tiling_shape_errors_and_gx_is_unaffected():
     assert hot.hot_act_buffer_bytes(cfg, 4 * 197 + 1, 64) == 0      # not a whole number of samples
     x, w, gy = make(2 * 197, 64, 24, seed=62)
     check_gx(hot, cfg, gy, w, True, "g_x with sample_tokens set")     # L need not be a multiple of n
+
+
+# ---- seeded random shapes and settings ----------------------------------------------------------
+
+def test_seeded_random_shapes_and_settings(exchange_wait, gemm_mode):
+    """120 small cases drawn with a fixed seed: block size, rank, kept-row list, per-sample
+    tiling, code widths, quantiser, rounding, column-kernel path (two-pass / single pass with
+    or without waiting) and GEMM work distribution, each against the oracle stage by stage."""
+    import random
+    hot = _hot()
+    rnd = random.Random(20250)
+    for it in range(120):
+        n = rnd.choice([16, 16, 32, 32, 64])
+        mode = rnd.choice(["gx", "gw", "fused", "gw", "gx"])
+        r = rnd.choice([1, 2, 3, n // 4, n // 2, n // 2, n // 2, n, rnd.randint(1, n)])
+        keep_idx = rnd.sample(range(n), r) if rnd.random() < 0.2 else None
+        S = 0
+        if mode == "gx":
+            L = rnd.randint(1, 1500)
+        elif mode == "gw" and rnd.random() < 0.3:
+            S = rnd.randint(1, 200)
+            L = S * rnd.randint(1, 8)
+        else:
+            L = n * rnd.randint(1, 60)
+        O = n * rnd.randint(1, 24) if mode in ("gx", "fused") else rnd.randint(1, 600)
+        I = rnd.randint(1, 400)
+        per_token = rnd.random() < 0.6
+        cfg = hot.Config(block=n, keep=r, keep_idx=keep_idx, gx_bits=rnd.choice([4, 4, 8]),
+                         rounding=rnd.choice([0, 1, 1]), sample_tokens=S)
+        wait_us, mode_g = rnd.choice([-1, 0, 200, 200]), rnd.choice([0, 0, 1, 2, 5])
+        x, w, gy = make(L, O, I, seed=1000 + it, gy_kind=rnd.choice(["chan_outlier", "tok_outlier", "normal"]))
+        exchange_wait(wait_us)
+        gemm_mode(mode_g)
+        what = f"random case {it} wait={wait_us} gemm={mode_g}"
+        if mode == "gx":
+            check_gx(hot, cfg, gy, w, per_token, what)
+        elif mode == "gw":
+            check_gw(hot, cfg, gy, x, what)
+        else:
+            check_fused(hot, cfg, gy, x, w, per_token, what)
