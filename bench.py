@@ -267,6 +267,9 @@ def main() -> int:
             k["GBps"] = round(mdl["bytes"] / (avg_us * 1e-6) / 1e9, 1)
             if "ops" in mdl:
                 k["TOPS"] = round(mdl["ops"] / (avg_us * 1e-6) / 1e12, 2)
+            # fraction of the published peak that bounds this kernel (HBM 8 TB/s or the MFMA peak)
+            k["frac"] = round(k["TOPS"] / mdl.get("peak", INT8_PEAK_TOPS) if mdl["bound"] == "mfma"
+                              else k["GBps"] / HBM_PEAK_GBS, 4)
         kernels[name] = k
     dominant = max((k for k in kernels if k in model), key=lambda k: kernels[k]["avg_us"])
     d, dm = kernels[dominant], model[dominant]
