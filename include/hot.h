@@ -14,8 +14,9 @@
  *     memory.  The caller owns every buffer; the library never allocates, frees
  *     or keeps device memory between calls.
  *   - `ws` is caller-provided device scratch of at least hot_workspace_bytes()
- *     bytes (256-byte aligned).  Its contents after a call are the packed
- *     operands of that call; the hot_debug_* calls decode them.
+ *     bytes, 256-byte aligned (checked: HOT_ERR_ARG otherwise).  Its first
+ *     HOT_WS_PREFIX_BYTES hold scalars, exchange slots and flags; the packed
+ *     operands of the call follow, and the hot_debug_* calls decode them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work and return without synchronising, except
  *     hot_select_quantizer, which waits for its own result.
@@ -85,7 +86,14 @@ const char* hot_status_string(hot_status s);
  * for an invalid config or shape. */
 size_t hot_act_buffer_bytes(const hot_config* cfg, int64_t L, int64_t I);
 
-/* Scratch bytes sufficient for every call below at this (L, O, I). 0 = invalid. */
+/* Bytes every workspace starts with (scales, abs-max exchange slots, split-K flags); the
+ * whole workspace of hot_compress_activation and hot_quantize_weight. */
+#define HOT_WS_PREFIX_BYTES 24832
+
+/* Scratch bytes sufficient for every call below at this (L, O, I); 0 = invalid.  A function
+ * of the configuration and the shape only: launch plans, and with them the scratch of the
+ * split-K GEMMs, are made for the 256 compute units of the MI355X whatever device is
+ * current. */
 size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t I);
 
 /*
@@ -93,7 +101,7 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
  *   x_hat = rows keep_idx of (H_n applied to every block of n consecutive tokens
  *   of x), INT8 with one abs-max scale for the tensor.
  * x: device [L x I] (in).  act_buf: device, hot_act_buffer_bytes() bytes (out).
- * ws: scratch as for the other calls (the first 17 KB are used).
+ * ws: at least HOT_WS_PREFIX_BYTES (nothing beyond them is touched).
  * Requires L % n == 0, L*r/n <= 133144.
  */
 hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_t L, int64_t I,
@@ -115,12 +123,15 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
  * only g_x is needed): quantise H.w once, reuse it every step.
  * hot_weight_buffer_bytes: a 256-byte header holding the scale, then I rows of O codes
  * (gx_bits each, row pitch rounded up to 128 bytes); 0 for an invalid config or shape.
- * hot_quantize_weight: w device [O x I] (in) -> wq_buf device (out); ws: the first 17 KB.
+ * hot_quantize_weight: w device [O x I] (in) -> wq_buf device (out); ws: at least
+ * HOT_WS_PREFIX_BYTES.
  * hot_linear_backward_gx_cached: hot_linear_backward_gx with the weight operand taken
- * from wq_buf (same cfg, O, I); same g_x bit for bit; ws may be smaller by the weight
- * codes.
+ * from wq_buf (same cfg, O, I); same g_x bit for bit.  Its ws holds no weight codes:
+ * hot_gx_cached_workspace_bytes() (never more than hot_workspace_bytes()) is enough, and a
+ * smaller one is HOT_ERR_WORKSPACE.
  */
 size_t hot_weight_buffer_bytes(const hot_config* cfg, int64_t O, int64_t I);
+size_t hot_gx_cached_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t I);
 hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O, int64_t I,
                                void* wq_buf, void* ws, size_t ws_bytes, void* stream);
 hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,

@@ -25,7 +25,7 @@ HOT_ROUND_NEAREST_EVEN, HOT_ROUND_PSEUDO_STOCHASTIC = 0, 1
 
 EXPORTS = (
     "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
-    "hot_weight_buffer_bytes", "hot_quantize_weight", "hot_linear_backward_gx_cached",
+    "hot_weight_buffer_bytes", "hot_gx_cached_workspace_bytes", "hot_quantize_weight", "hot_linear_backward_gx_cached",
     "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
     "hot_linear_backward", "hot_select_quantizer", "hot_debug_unpack_activation",
     "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us",
@@ -33,6 +33,7 @@ EXPORTS = (
     "hot_debug_stage_name", "hot_debug_probe",
 )
 HOT_NUM_STAGES = 15
+HOT_WS_PREFIX_BYTES = 24832
 
 
 class hot_config(C.Structure):
@@ -87,10 +88,12 @@ def lib() -> C.CDLL:
         l.hot_debug_probe.argtypes = [C.c_int, vp, sz, C.c_int, vp]
         l.hot_weight_buffer_bytes.argtypes = [cfgp, i64, i64]
         l.hot_weight_buffer_bytes.restype = sz
+        l.hot_gx_cached_workspace_bytes.argtypes = [cfgp, i64, i64, i64]
+        l.hot_gx_cached_workspace_bytes.restype = sz
         l.hot_quantize_weight.argtypes = [cfgp, vp, i64, i64, vp, vp, sz, vp]
         l.hot_linear_backward_gx_cached.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
         l.hot_debug_unpack_weight.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
-        for name in EXPORTS[5:]:
+        for name in EXPORTS[6:]:
             if name != "hot_debug_stage_name":
                 getattr(l, name).restype = C.c_int
         l.hot_debug_stage_name.argtypes = [C.c_int]
@@ -180,6 +183,10 @@ def alloc_act_buffer(cfg: Config, L: int, I: int, device="cuda") -> torch.Tensor
 
 def hot_weight_buffer_bytes(cfg: Config, O: int, I: int) -> int:
     return int(lib().hot_weight_buffer_bytes(C.byref(cfg.c()), O, I))
+
+
+def hot_gx_cached_workspace_bytes(cfg: Config, L: int, O: int, I: int) -> int:
+    return int(lib().hot_gx_cached_workspace_bytes(C.byref(cfg.c()), L, O, I))
 
 
 def alloc_weight_buffer(cfg: Config, O: int, I: int, device="cuda") -> torch.Tensor:

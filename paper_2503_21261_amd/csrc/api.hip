@@ -23,6 +23,9 @@ int row_sign_changes(int n, int k) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// The workspace: its sub-regions (exchange slots, flags, operand rows) sit at multiples of 128
+// and 256 bytes from its start and are accessed as 8- and 16-byte words.
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 }  // namespace
 
@@ -142,6 +145,11 @@ bool gx_shape_ok(const Config& c, int64_t L, int64_t O, int64_t I) {
   return L >= 1 && I >= 1 && O >= c.n && O % c.n == 0 && L < (1ll << 31) && I < (1ll << 31) &&
          O <= (c.gx_bits == 4 ? kMaxK4 : kMaxK8);
 }
+// With the weight codes in a buffer of their own the workspace holds no weight rows: the
+// GEMM scratch follows the g_y codes directly.
+size_t gx_cached_partial(const GxLayout& g) { return (size_t)round_up((int64_t)g.qw, 256); }
+size_t gx_cached_total(const GxLayout& g) { return gx_cached_partial(g) + (g.total - g.partial); }
+
 bool tok_shape_ok(const Config& c, int64_t L, int64_t cols) {
   // the int32 bound on L' only binds integer accumulators; bfloat16 operands sum in fp32
   const int64_t nblk = row_tiling(c, L).nblk;
@@ -254,7 +262,7 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   Config c;
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
-  if (!x || !act_buf || !ws || !aligned16(x) || !aligned16(act_buf) || !aligned16(ws)) return HOT_ERR_ARG;
+  if (!x || !act_buf || !ws || !aligned16(x) || !aligned16(act_buf) || !aligned256(ws)) return HOT_ERR_ARG;
   if (!tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
   if (ws_bytes < (size_t)kWsPrefix) return HOT_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -276,12 +284,18 @@ size_t hot_weight_buffer_bytes(const hot_config* cfg, int64_t O, int64_t I) {
   return weight_layout(c, O, I).total;
 }
 
+size_t hot_gx_cached_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t I) {
+  Config c;
+  if (resolve_config(cfg, &c) != HOT_OK || !gx_shape_ok(c, L, O, I)) return 0;
+  return gx_cached_total(gx_layout(c, L, O, I));
+}
+
 hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O, int64_t I,
                                void* wq_buf, void* ws, size_t ws_bytes, void* stream) {
   Config c;
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
-  if (!w || !wq_buf || !ws || !aligned16(w) || !aligned16(wq_buf) || !aligned16(ws)) return HOT_ERR_ARG;
+  if (!w || !wq_buf || !ws || !aligned16(w) || !aligned16(wq_buf) || !aligned256(ws)) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, 1, O, I)) return HOT_ERR_SHAPE;
   if (ws_bytes < (size_t)kWsPrefix) return HOT_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -342,8 +356,8 @@ hot_status gx_operands(const Config& c, const float* g_y, const float* w, int64_
 // g_x path, second half: multiply the operand at g.qg with quantised weights, dequantise.
 hot_status gx_gemm(const Config& c, const uint8_t* qw, const float* s_w, int64_t L, int64_t I,
                    hot_quantizer gy_quantizer, float* g_x, uint8_t* base, const GxLayout& g,
-                   hipStream_t s) {
-  HOT_TRY(gemm(base + g.qg, qw, L, I, g.pitch, c.gx_bits, base, g.partial, nullptr, g_x,
+                   size_t partial_off, hipStream_t s) {
+  HOT_TRY(gemm(base + g.qg, qw, L, I, g.pitch, c.gx_bits, base, partial_off, nullptr, g_x,
                (const float*)(base + g.sg), gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
@@ -369,7 +383,7 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   Config c;
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
-  if (!g_y || !w || !g_x || !ws || !aligned16(g_y) || !aligned16(w) || !aligned16(g_x) || !aligned16(ws))
+  if (!g_y || !w || !g_x || !ws || !aligned16(g_y) || !aligned16(w) || !aligned16(g_x) || !aligned256(ws))
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
@@ -379,7 +393,7 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   uint8_t* base = (uint8_t*)ws;
   st = gx_operands(c, g_y, w, L, O, I, gy_quantizer, base, g, s);
   if (st != HOT_OK) return st;
-  return gx_gemm(c, base + g.qw, (const float*)(base + g.scalars), L, I, gy_quantizer, g_x, base, g, s);
+  return gx_gemm(c, base + g.qw, (const float*)(base + g.scalars), L, I, gy_quantizer, g_x, base, g, g.partial, s);
 }
 
 hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
@@ -390,17 +404,18 @@ hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
   if (!g_y || !wq_buf || !g_x || !ws || !aligned16(g_y) || !aligned16(wq_buf) || !aligned16(g_x) ||
-      !aligned16(ws))
+      !aligned256(ws))
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
   const GxLayout g = gx_layout(c, L, O, I);
-  if (ws_bytes < g.qw) return HOT_ERR_WORKSPACE;   // the weight-code region of ws is not needed
+  if (ws_bytes < gx_cached_total(g)) return HOT_ERR_WORKSPACE;
   const WeightLayout wl = weight_layout(c, O, I);
   const uint8_t* wb = (const uint8_t*)wq_buf;
   st = gx_rows(c, g_y, L, O, gy_quantizer, (uint8_t*)ws, g, (hipStream_t)stream);
   if (st != HOT_OK) return st;
-  return gx_gemm(c, wb + wl.codes, (const float*)wb, L, I, gy_quantizer, g_x, (uint8_t*)ws, g, (hipStream_t)stream);
+  return gx_gemm(c, wb + wl.codes, (const float*)wb, L, I, gy_quantizer, g_x, (uint8_t*)ws, g,
+                 gx_cached_partial(g), (hipStream_t)stream);
 }
 
 hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const void* act_buf,
@@ -410,7 +425,7 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
   if (!g_y || !act_buf || !g_w || !ws || !aligned16(g_y) || !aligned16(act_buf) || !aligned16(g_w) ||
-      !aligned16(ws))
+      !aligned256(ws))
     return HOT_ERR_ARG;
   if (!tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
   const GwLayout g = gw_layout(c, L, O, I);
@@ -438,7 +453,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
   if (!g_y || !w || !act_buf || !g_x || !g_w || !ws || !aligned16(g_y) || !aligned16(w) ||
-      !aligned16(act_buf) || !aligned16(g_x) || !aligned16(g_w) || !aligned16(ws))
+      !aligned16(act_buf) || !aligned16(g_x) || !aligned16(g_w) || !aligned256(ws))
     return HOT_ERR_ARG;
   if (gy_quantizer != HOT_Q_PER_TOKEN && gy_quantizer != HOT_Q_PER_TENSOR) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, I) || !tok_shape_ok(c, L, O) || !tok_shape_ok(c, L, I)) return HOT_ERR_SHAPE;
@@ -480,7 +495,7 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
   Config c;
   hot_status st = resolve_config(cfg, &c);
   if (st != HOT_OK) return st;
-  if (!g_y || !choice || !ws || !aligned16(g_y) || !aligned16(ws)) return HOT_ERR_ARG;
+  if (!g_y || !choice || !ws || !aligned16(g_y) || !aligned256(ws)) return HOT_ERR_ARG;
   if (!gx_shape_ok(c, L, O, 1)) return HOT_ERR_SHAPE;
   const SelLayout l = sel_layout(c, L, O);
   if (ws_bytes < l.total) return HOT_ERR_WORKSPACE;

@@ -49,6 +49,7 @@ constexpr int64_t kPartialBytes = 2048 * 4;
 constexpr int kMaxSplitSlots = 1024;
 constexpr int64_t kGemmFlagsOffset = kHeaderBytes + 2 * kPartialBytes;
 constexpr int64_t kWsPrefix = kGemmFlagsOffset + kMaxSplitSlots * 8;
+static_assert(kWsPrefix == HOT_WS_PREFIX_BYTES, "hot.h documents the prefix size");
 // |code products| summed over K must fit int32 (INT4 operands are fed to the
 // matrix cores as 16 x code, so their bound carries a factor 256).
 constexpr int64_t kMaxK8 = 133144;   // 127^2 * K < 2^31

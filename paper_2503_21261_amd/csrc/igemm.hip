@@ -57,17 +57,12 @@ namespace {
 std::atomic<int> g_gemm_mode{0};   // 0: cost model, 1: never split K, s >= 2: s slices where possible
 std::atomic<int> g_gemm_wait_us{200};
 
-int compute_units() {
-  static std::atomic<int> cus{0};
-  int c = cus.load(std::memory_order_relaxed);
-  if (c > 0) return c;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c <= 0)
-    c = 256;   // planning only (sizes a scratch region); nothing is launched from here
-  cus.store(c, std::memory_order_relaxed);
-  return c;
-}
+// Compute units the launch plans are made for: those of the MI355X.  A constant rather than
+// a device query, so that workspace sizes are a function of the configuration and the shape
+// alone; on a part with fewer units the plans stay correct (every wait for another workgroup is
+// bounded), only less well fitted.
+constexpr int kPlanComputeUnits = 256;
+int compute_units() { return kPlanComputeUnits; }
 
 // Most slices a 128x128-tile GEMM may be cut into: at least 4 K stages per slice, and no more
 // image slots than the workspace has flags for.

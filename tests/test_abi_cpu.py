@@ -122,6 +122,40 @@ def test_argument_shape_and_workspace_errors_precede_any_launch():
     assert hot.status_string(hot.HOT_ERR_WORKSPACE) == "workspace too small"
 
 
+def test_cached_gx_workspace_covers_the_split_k_scratch():
+    """A g_x GEMM with few output tiles splits K and hands partial sums over through scratch
+    that follows the g_y codes (L=512, O=I=4096: 128 tiles of 128x128 in 4 slices, 25 MB of images).
+    The cached call's workspace is smaller than the uncached one by the weight rows only; a
+    workspace that ends with the g_y codes is refused before any launch."""
+    lib, cfg = hot.lib(), hot.Config()
+    c = C.byref(cfg.c())
+    fake = C.c_void_p(4096)
+    L, O, I = 512, 4096, 4096
+    pitch = O // 2
+    codes_end = hot.HOT_WS_PREFIX_BYTES + L * 4 + L * pitch
+    full, cached = hot.hot_workspace_bytes(cfg, L, O, I), hot.hot_gx_cached_workspace_bytes(cfg, L, O, I)
+    scratch = 128 * 7 * 128 * 128 * 4       # sized for the deepest split a forced mode may ask for
+    assert cached == codes_end + scratch
+    assert full >= cached + I * pitch
+    for too_small in (codes_end, codes_end + 128 * 3 * 128 * 128 * 4, cached - 1):
+        assert lib.hot_linear_backward_gx_cached(c, fake, fake, L, O, I, 1, fake, fake, too_small, None) \
+            == hot.HOT_ERR_WORKSPACE
+    # many output tiles: no split, no scratch, the workspace ends with the g_y codes
+    L = 65536
+    assert hot.hot_gx_cached_workspace_bytes(cfg, L, O, I) == hot.HOT_WS_PREFIX_BYTES + L * 4 + L * pitch
+    assert hot.hot_gx_cached_workspace_bytes(cfg, 64, 72, 64) == 0
+
+
+def test_workspace_must_be_256_byte_aligned():
+    lib, cfg = hot.lib(), hot.Config()
+    c = C.byref(cfg.c())
+    fake, odd = C.c_void_p(4096), C.c_void_p(4096 + 128)
+    big = 1 << 40
+    assert lib.hot_linear_backward_gx(c, fake, fake, 64, 64, 64, 1, fake, odd, big, None) == hot.HOT_ERR_ARG
+    assert lib.hot_linear_backward_gw(c, fake, fake, 64, 64, 64, fake, odd, big, None) == hot.HOT_ERR_ARG
+    assert lib.hot_compress_activation(c, fake, 64, 64, fake, odd, big, None) == hot.HOT_ERR_ARG
+
+
 def test_binding_refuses_host_tensors():
     import torch
     cfg = hot.Config()

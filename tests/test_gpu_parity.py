@@ -514,30 +514,42 @@ def test_fused_backward_config1_full():
 
 # ---- frozen weights: H.w quantised once, g_x only (Sec. 5.3) -------------------------
 
-@pytest.mark.parametrize("n,bits,per_token", [(16, 4, True), (32, 4, False), (64, 8, True)])
-def test_frozen_weight_gx_matches_oracle_and_uncached_call(n, bits, per_token):
+@pytest.mark.parametrize("n,bits,per_token,shape", [(16, 4, True, (264, 448, 136)), (32, 4, False, (264, 448, 136)),
+                                                    (64, 8, True, (264, 448, 136)),
+                                                    # few output tiles, long K: the GEMM splits K and its
+                                                    # scratch follows the g_y codes in the smaller workspace
+                                                    (16, 4, True, (264, 2048, 384)), (32, 8, False, (300, 2048, 200))])
+def test_frozen_weight_gx_matches_oracle_and_uncached_call(n, bits, per_token, shape):
     hot = _hot()
-    L, O, I = 264, 448, 136
+    L, O, I = shape
     x, w, gy = make(L, O, I, seed=31)
     cfg = hot.Config(block=n, keep=n // 2, gx_bits=bits)
     _say(f"[gx cached] L={L} O={O} I={I} n={n} bits={bits} token={per_token}")
     ref = oracle.backward_gx(gy.numpy(), w.numpy(), n, bits=bits, per_token=per_token, rounding=cfg.rounding)
     q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
     wd = w.cuda()
-    ws = hot.alloc_workspace(cfg, L, O, I)
+    ws0 = hot.alloc_workspace(cfg, L, O, I)
     wq = hot.alloc_weight_buffer(cfg, O, I)
-    hot.hot_quantize_weight(cfg, wd, wq, ws)
+    hot.hot_quantize_weight(cfg, wd, wq, ws0[:hot.HOT_WS_PREFIX_BYTES])
     codes, sw = hot.hot_debug_unpack_weight(cfg, wq, O, I)
     torch.cuda.synchronize()
     assert np.array_equal(codes.cpu().numpy(), ref["qw"]) and bits_equal(sw.cpu().numpy(), ref["sw"])
-    ws.fill_(0x33)   # nothing of the weight pass may be needed from ws afterwards
+    # the cached call's own, smaller workspace, placed so that anything written past its end
+    # lands in a guard region
+    need = hot.hot_gx_cached_workspace_bytes(cfg, L, O, I)
+    assert 0 < need <= ws0.numel() - O * I * bits // 8
+    guarded = torch.full((need + 4096,), 0x33, dtype=torch.uint8, device="cuda")
+    ws = guarded[:need]
     gx = torch.empty((L, I), device="cuda")
     for step in range(2):   # second step: another g_y against the same cached weights
         g = gy if step == 0 else hot_inputs.make_gy("t4", L, O, 32, "step2")
         r = ref if step == 0 else oracle.backward_gx(g.numpy(), w.numpy(), n, bits=bits, per_token=per_token,
                                                      rounding=cfg.rounding)
         hot.hot_linear_backward_gx_cached(cfg, g.cuda(), wq, I, q, gx, ws)
-        taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q, want_acc=False)
+        torch.cuda.synchronize()
+        assert (guarded[need:] == 0x33).all().item(), "written past the documented workspace size"
+        ws0[:need].copy_(ws)    # the operand view decodes a full-size workspace
+        taps = hot.hot_debug_gx_operands(cfg, ws0, L, O, I, q, want_acc=False)
         torch.cuda.synchronize()
         assert np.array_equal(taps["qg"].cpu().numpy(), r["qg"]) and bits_equal(taps["sg"].cpu().numpy(), r["sg"])
         assert_close_maxnorm(gx.cpu().numpy(), r["g_x"], f"cached g_x step {step}")
