@@ -45,7 +45,9 @@ typedef enum {
   HOT_ERR_SHAPE = 2,      /* a size the method or the int32 accumulators forbid  */
   HOT_ERR_WORKSPACE = 3,  /* ws_bytes smaller than hot_workspace_bytes()         */
   HOT_ERR_DEVICE = 4,     /* a HIP runtime call failed                           */
-  HOT_ERR_UNIMPLEMENTED = 5
+  HOT_ERR_UNIMPLEMENTED = 5,
+  HOT_ERR_SCRATCH_LIMIT = 6 /* hot_linear_backward_gx_noalloc: the shape needs more than
+                               HOT_NOALLOC_SCRATCH_BYTES of scratch                      */
 } hot_status;
 
 /* Sec. 5.2.2: granularity of the scale of the rotated g_y. */
@@ -117,6 +119,27 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
 hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const float* w,
                                   int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
                                   float* g_x, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * hot_linear_backward_gx for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture set-up, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same g_x bit for bit, but the scratch is
+ * an array inside the library's code object (HOT_NOALLOC_SCRATCH_BYTES, 64 MiB, held on
+ * every GPU the library runs on until the process ends) instead of `ws`.  The call
+ * allocates and frees nothing, on the device or through any library.
+ *   - A shape whose hot_linear_backward_gx workspace layout exceeds the array returns
+ *     HOT_ERR_SCRATCH_LIMIT before anything is launched (ViT-B fc1 at 12608 tokens needs
+ *     59.5 MB and fits; 50432 tokens do not).
+ *   - The array belongs to the device that is current at the call; `stream` must be a
+ *     stream of that device.
+ *   - All calls on one GPU share the array, which keeps the last call's contents.  Nothing
+ *     in it has to be cleared between calls, but two calls that overlap in time on one GPU
+ *     (different streams, different threads) race on it: order them.
+ */
+#define HOT_NOALLOC_SCRATCH_BYTES (64u << 20)
+hot_status hot_linear_backward_gx_noalloc(const hot_config* cfg, const float* g_y, const float* w,
+                                          int64_t L, int64_t O, int64_t I,
+                                          hot_quantizer gy_quantizer, float* g_x, void* stream);
 
 /*
  * Frozen weights (Sec. 5.3: with LoRA-style fine-tuning the base weights stay fixed and

@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libhot.so")
 
 HOT_OK = 0
 HOT_ERR_ARG, HOT_ERR_SHAPE, HOT_ERR_WORKSPACE, HOT_ERR_DEVICE, HOT_ERR_UNIMPLEMENTED = 1, 2, 3, 4, 5
+HOT_ERR_SCRATCH_LIMIT = 6
+HOT_NOALLOC_SCRATCH_BYTES = 64 << 20
 HOT_Q_PER_TENSOR, HOT_Q_PER_TOKEN = 0, 1
 HOT_ROUND_NEAREST_EVEN, HOT_ROUND_PSEUDO_STOCHASTIC = 0, 1
 
@@ -27,7 +29,7 @@ EXPORTS = (
     "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
     "hot_weight_buffer_bytes", "hot_gx_cached_workspace_bytes", "hot_quantize_weight", "hot_linear_backward_gx_cached",
     "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
-    "hot_linear_backward", "hot_select_quantizer", "hot_debug_unpack_activation",
+    "hot_linear_backward", "hot_linear_backward_gx_noalloc", "hot_select_quantizer", "hot_debug_unpack_activation",
     "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us",
     "hot_debug_set_backward_strategy", "hot_debug_set_gemm_mode", "hot_debug_profile_begin", "hot_debug_profile_end",
     "hot_debug_stage_name", "hot_debug_probe",
@@ -72,6 +74,7 @@ def lib() -> C.CDLL:
         l.hot_workspace_bytes.restype = sz
         l.hot_compress_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, sz, vp]
         l.hot_linear_backward_gx.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+        l.hot_linear_backward_gx_noalloc.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp]
         l.hot_linear_backward_gw.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, sz, vp]
         l.hot_linear_backward.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, sz, vp]
         l.hot_select_quantizer.argtypes = [cfgp, vp, i64, i64, C.POINTER(C.c_int),
@@ -247,6 +250,18 @@ def hot_linear_backward_gx(cfg: Config, g_y: torch.Tensor, w: torch.Tensor, gy_q
                                       int(gy_quantizer), _ptr(g_x), _ptr(ws), ws.numel(),
                                       _stream(stream))
     _check(st, "hot_linear_backward_gx")
+    return g_x
+
+
+def hot_linear_backward_gx_noalloc(cfg: Config, g_y: torch.Tensor, w: torch.Tensor, gy_quantizer: int,
+                                   g_x: torch.Tensor, stream=None) -> torch.Tensor:
+    """hot_linear_backward_gx with the library's built-in scratch instead of a workspace."""
+    L, O = g_y.shape
+    I = w.shape[1]
+    _dev_f32(g_y, (L, O), "g_y"); _dev_f32(w, (O, I), "w"); _dev_f32(g_x, (L, I), "g_x")
+    st = lib().hot_linear_backward_gx_noalloc(C.byref(cfg.c()), _ptr(g_y), _ptr(w), L, O, I,
+                                              int(gy_quantizer), _ptr(g_x), _stream(stream))
+    _check(st, "hot_linear_backward_gx_noalloc")
     return g_x
 
 

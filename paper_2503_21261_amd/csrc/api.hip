@@ -226,6 +226,7 @@ const char* hot_status_string(hot_status s) {
     case HOT_ERR_WORKSPACE: return "workspace too small";
     case HOT_ERR_DEVICE: return "HIP runtime error";
     case HOT_ERR_UNIMPLEMENTED: return "not implemented";
+    case HOT_ERR_SCRATCH_LIMIT: return "shape needs more scratch than the library's built-in buffer holds";
   }
   return "unknown status";
 }
@@ -377,23 +378,84 @@ hot_status gw_operand(const Config& c, const float* g_y, int64_t L, int64_t O, u
 
 }  // namespace
 
+namespace {
+
+// Checks shared by the two forms of the g_x call (everything but the scratch).
+hot_status gx_check(const hot_config* cfg, const float* g_y, const float* w, int64_t L, int64_t O,
+                    int64_t I, hot_quantizer gy_quantizer, const float* g_x, Config* c) {
+  hot_status st = resolve_config(cfg, c);
+  if (st != HOT_OK) return st;
+  if (!g_y || !w || !g_x || !aligned16(g_y) || !aligned16(w) || !aligned16(g_x)) return HOT_ERR_ARG;
+  if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
+  if (!gx_shape_ok(*c, L, O, I)) return HOT_ERR_SHAPE;
+  return HOT_OK;
+}
+
+hot_status gx_run(const Config& c, const float* g_y, const float* w, int64_t L, int64_t O, int64_t I,
+                  hot_quantizer gy_quantizer, float* g_x, uint8_t* base, const GxLayout& g, hipStream_t s) {
+  hot_status st = gx_operands(c, g_y, w, L, O, I, gy_quantizer, base, g, s);
+  if (st != HOT_OK) return st;
+  return gx_gemm(c, base + g.qw, (const float*)(base + g.scalars), L, I, gy_quantizer, g_x, base, g, g.partial, s);
+}
+
+}  // namespace
+
 hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const float* w,
                                   int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
                                   float* g_x, void* ws, size_t ws_bytes, void* stream) {
   Config c;
-  hot_status st = resolve_config(cfg, &c);
+  hot_status st = gx_check(cfg, g_y, w, L, O, I, gy_quantizer, g_x, &c);
   if (st != HOT_OK) return st;
-  if (!g_y || !w || !g_x || !ws || !aligned16(g_y) || !aligned16(w) || !aligned16(g_x) || !aligned256(ws))
-    return HOT_ERR_ARG;
-  if (gy_quantizer != HOT_Q_PER_TENSOR && gy_quantizer != HOT_Q_PER_TOKEN) return HOT_ERR_ARG;
-  if (!gx_shape_ok(c, L, O, I)) return HOT_ERR_SHAPE;
+  if (!ws || !aligned256(ws)) return HOT_ERR_ARG;
   const GxLayout g = gx_layout(c, L, O, I);
   if (ws_bytes < g.total) return HOT_ERR_WORKSPACE;
-  hipStream_t s = (hipStream_t)stream;
-  uint8_t* base = (uint8_t*)ws;
-  st = gx_operands(c, g_y, w, L, O, I, gy_quantizer, base, g, s);
+  return gx_run(c, g_y, w, L, O, I, gy_quantizer, g_x, (uint8_t*)ws, g, (hipStream_t)stream);
+}
+
+// ---- the g_x call for callers that cannot allocate ---------------------------------------
+//
+// The workspace of hot_linear_backward_gx (scalars, exchange slots, split-K flags, both packed
+// operands, split-K images) lives in this array instead of a caller's buffer.  Every GPU the
+// library runs on holds its own copy from the moment the code object is loaded until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address it returns (one per device) is what kernels, copies and fills are given.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[HOT_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+hot_status scratch_of_current_device(uint8_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HOT_ERR_DEVICE;
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HOT_ERR_DEVICE;
+    if ((reinterpret_cast<uintptr_t>(p) & 255u) != 0) return HOT_ERR_DEVICE;
+    g_scratch_addr[dev].store(p, std::memory_order_release);   // two threads racing here store the same address
+  }
+  *out = (uint8_t*)p;
+  return HOT_OK;
+}
+
+}  // namespace
+
+hot_status hot_linear_backward_gx_noalloc(const hot_config* cfg, const float* g_y, const float* w,
+                                          int64_t L, int64_t O, int64_t I, hot_quantizer gy_quantizer,
+                                          float* g_x, void* stream) {
+  Config c;
+  hot_status st = gx_check(cfg, g_y, w, L, O, I, gy_quantizer, g_x, &c);
   if (st != HOT_OK) return st;
-  return gx_gemm(c, base + g.qw, (const float*)(base + g.scalars), L, I, gy_quantizer, g_x, base, g, g.partial, s);
+  const GxLayout g = gx_layout(c, L, O, I);
+  if (g.total > (size_t)HOT_NOALLOC_SCRATCH_BYTES) return HOT_ERR_SCRATCH_LIMIT;
+  uint8_t* base = nullptr;
+  st = scratch_of_current_device(&base);
+  if (st != HOT_OK) return st;
+  // Nothing in the scratch has to start at zero: exchange slots and split-K flags are told
+  // from an earlier call's by a per-launch tag, everything else is written before it is read.
+  return gx_run(c, g_y, w, L, O, I, gy_quantizer, g_x, base, g, (hipStream_t)stream);
 }
 
 hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y,
