@@ -28,9 +28,35 @@ def _say(*a):
 
 
 def assert_close_maxnorm(got, ref, what):
+    """The stated bound, 1e-5 of max|ref| on every element, and an element-wise one that also
+    holds small entries to their own size: |got - ref| <= 1e-5 |ref| + 1e-6 max|ref| (the
+    epilogue's own error is about 2e-7 relative: one int->float conversion, two multiplies)."""
     denom = np.max(np.abs(ref))
-    err = np.max(np.abs(got.astype(np.float64) - ref))
+    diff = np.abs(got.astype(np.float64) - ref)
+    err = np.max(diff)
     assert err <= REL_TOL * denom + 1e-300, f"{what}: max err {err:.3e} vs max|ref| {denom:.3e}"
+    excess = diff - (REL_TOL * np.abs(ref) + 1e-6 * denom)
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0, (f"{what}: element {worst}: got {got[worst]!r}, ref {ref[worst]!r}, "
+                                f"max|ref| {denom:.3e}")
+
+
+def dequant_fp32(acc, s_row, s_col, n):
+    """The epilogue's own arithmetic, in fp32 in its order: float(acc) * (s_row * (s_col / n));
+    1/n is a power of two, so every step is one IEEE operation (the INT4 kernels carry 256 x acc
+    and fold 1/256 into the factor: exact scalings that change no rounding)."""
+    cs = np.float32(s_col) * np.float32(1.0 / n)
+    rs = np.asarray(s_row, np.float32).reshape(-1, 1) * cs
+    return np.asarray(acc).astype(np.float32) * rs
+
+
+def assert_output_is_dequantised_accumulator(out, acc, s_row, s_col, n, what):
+    """Ties the output of a production launch (fused epilogue, split-K hand-over) to the
+    integer accumulators, which are compared exactly with the oracle: same bits everywhere.
+    `out`, `acc`: device tensors; s_row: device [M] or [1]; s_col: device [1]."""
+    cs = s_col.to(torch.float32) * torch.tensor(1.0 / n, dtype=torch.float32, device=out.device)
+    rs = s_row.to(torch.float32).reshape(-1, 1) * cs
+    assert torch.equal(out, acc.to(torch.float32) * rs), f"{what}: output is not float(acc) * scales"
 
 
 def bits_equal(a, b):
@@ -57,6 +83,9 @@ def check_gx(hot, cfg, gy, w, per_token, what):
     assert np.array_equal(taps["qw"].cpu().numpy(), ref["qw"]), f"{what}: w codes differ"
     assert np.array_equal(taps["acc"].cpu().numpy().astype(np.int64), ref["acc"]), f"{what}: accumulators differ"
     assert_close_maxnorm(gx.cpu().numpy(), ref["g_x"], what + " g_x")
+    assert_output_is_dequantised_accumulator(gx, taps["acc"], taps["sg"], taps["sw"], cfg.block, what + " g_x")
+    assert np.array_equal(gx.cpu().numpy(), dequant_fp32(ref["acc"], ref["sg"], ref["sw"][0], cfg.block)), \
+        f"{what}: g_x is not the fp32 dequantisation of the oracle's accumulators"
     return ref, gx
 
 
@@ -88,6 +117,9 @@ def check_gw(hot, cfg, gy, x, what):
     assert np.array_equal(taps["qg"].cpu().numpy(), ref["qg"]), f"{what}: HLA(g_y) codes differ"
     assert np.array_equal(taps["acc"].cpu().numpy().astype(np.int64), ref["acc"]), f"{what}: accumulators differ"
     assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w")
+    assert_output_is_dequantised_accumulator(gw, taps["acc"], taps["sg"], sx, cfg.block, what + " g_w")
+    assert np.array_equal(gw.cpu().numpy(), dequant_fp32(ref["acc"], [ref["sg"]], sx_ref, cfg.block)), \
+        f"{what}: g_w is not the fp32 dequantisation of the oracle's accumulators"
     return ref, gw
 
 
@@ -337,69 +369,150 @@ def _vecmat_exact(u, A, chunk=16384):
     return out
 
 
-def check_full_size_sampled(hot, wl, layer, what, per_token=True):
-    """One layer at its full size: every code and scale of every operand is compared with the
-    oracle; both integer products are checked on all outputs through exact Freivalds identities
-    C v = A (B v) and on sampled output rows against the oracle's GEMM, whose dequantised rows
-    bound the fp32 outputs."""
-    L, O, I = layer.L, layer.O, layer.I
-    n, r = wl.block, wl.keep
-    cfg = hot.Config(block=n, keep=r)
-    xd, wd, gyd = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
-    x, w, gy = xd.cpu().numpy(), wd.cpu().numpy(), gyd.cpu().numpy()
-    rng = np.random.default_rng(5)
+class FullSizeRefs:
+    """Oracle stages of one layer at its full size, computed once: every code and scale of the
+    four quantised operands, and what the integer products must satisfy: the exact Freivalds
+    images A (B v) and (u A) B for random small-integer vectors (checked on all outputs), and
+    the oracle's own GEMM on sampled output rows, whose dequantised rows bound the fp32 outputs."""
+
+    def __init__(self, x, w, gy, n, r, per_token, seed=5):
+        self.n, self.r, self.per_token = n, r, per_token
+        L, O = gy.shape
+        I = w.shape[1]
+        self.L, self.O, self.I = L, O, I
+        rng = np.random.default_rng(seed)
+        PSR = oracle.PSEUDO_STOCHASTIC
+        self.qg, self.sg = oracle.quantize(oracle.transform_rows(gy, n), 4, per_token, PSR)
+        self.qw, self.sw = oracle.quantize(oracle.hla(w, n, n, np.arange(n)), 4, False, PSR)
+        keep = oracle.lowpass_index(n, r)
+        self.xc, self.sx = oracle.compress_activation(x, n, r)
+        self.gh, self.sh = oracle.quantize(oracle.hla(gy, n, r, keep), 8, False, PSR)
+        # g_x product [L x I] = qg [L x O] . qw [O x I]
+        self.vx = rng.integers(-2048, 2048, size=I)
+        self.ux = rng.integers(-2048, 2048, size=L)
+        self.gx_Cv = _matvec_exact(self.qg, _matvec_exact(self.qw, self.vx))
+        self.gx_uC = _vecmat_exact(_vecmat_exact(self.ux, self.qg), self.qw)
+        self.rows = np.unique(np.concatenate([np.arange(0, 256), rng.integers(0, L, 512), np.arange(L - 200, L)]))
+        self.gx_acc_rows, bad = oracle.igemm_nn(self.qg[self.rows], self.qw)
+        assert bad == 0
+        self.gx_rows = oracle.dequant(self.gx_acc_rows, self.sg[self.rows] if per_token else self.sg, self.sw[0], n)
+        # g_w product [O x I] = gh^T [O x L'] . xc [L' x I]
+        self.vw = rng.integers(-2048, 2048, size=I)
+        self.uw = rng.integers(-2048, 2048, size=O)
+        self.gw_Cv = _vecmat_exact(_matvec_exact(self.xc, self.vw), self.gh)
+        self.gw_uC = _vecmat_exact(_matvec_exact(self.gh, self.uw), self.xc)
+        self.orow = np.unique(np.concatenate([np.arange(0, 64), rng.integers(0, O, 64), np.arange(O - 40, O)]))
+        self.gw_acc_rows, bad = oracle.igemm_tn(np.ascontiguousarray(self.gh[:, self.orow]), self.xc)
+        assert bad == 0
+        self.gw_rows = oracle.dequant(self.gw_acc_rows, self.sh, self.sx, n)
+
+    def check_gx_operands(self, qg, sg, qw, sw, what):
+        assert np.array_equal(qg.cpu().numpy(), self.qg), f"{what}: g_y codes differ"
+        assert bits_equal(sg.cpu().numpy(), self.sg), f"{what}: g_y scales differ"
+        assert np.array_equal(qw.cpu().numpy(), self.qw), f"{what}: w codes differ"
+        assert bits_equal(sw.cpu().numpy(), self.sw), f"{what}: w scale differs"
+
+    def check_gx_product(self, acc_d, gx_d, sg_d, sw_d, what):
+        acc = acc_d.cpu().numpy()
+        assert np.array_equal(_matvec_exact(acc, self.vx), self.gx_Cv), f"{what}: g_x accumulators, C v"
+        assert np.array_equal(_vecmat_exact(self.ux, acc), self.gx_uC), f"{what}: g_x accumulators, u C"
+        assert np.array_equal(acc[self.rows].astype(np.int64), self.gx_acc_rows), f"{what}: g_x accumulator rows"
+        del acc
+        self.check_gx_output(gx_d, what)
+        assert_output_is_dequantised_accumulator(gx_d, acc_d, sg_d, sw_d, self.n, what + " g_x")
+
+    def check_gx_output(self, gx_d, what):
+        got = gx_d[torch.from_numpy(self.rows).cuda()].cpu().numpy()
+        assert_close_maxnorm(got, self.gx_rows, what + " g_x rows")
+        want = dequant_fp32(self.gx_acc_rows, self.sg[self.rows] if self.per_token else self.sg, self.sw[0], self.n)
+        assert np.array_equal(got, want), f"{what}: g_x rows are not the fp32 dequantisation of the oracle's sums"
+
+    def check_gw_operands(self, codes, sx, qgh, sgh, what):
+        if codes is not None:
+            assert bits_equal(sx.cpu().numpy(), [self.sx]) and np.array_equal(codes.cpu().numpy(), self.xc), \
+                f"{what}: compressed activation differs"
+        assert bits_equal(sgh.cpu().numpy(), self.sh), f"{what}: HLA(g_y) scale differs"
+        assert np.array_equal(qgh.cpu().numpy(), self.gh), f"{what}: HLA(g_y) codes differ"
+
+    def check_gw_product(self, acc_d, gw_d, sgh_d, sx_d, what):
+        acc = acc_d.cpu().numpy()
+        assert np.array_equal(_matvec_exact(acc, self.vw), self.gw_Cv), f"{what}: g_w accumulators, C v"
+        assert np.array_equal(_vecmat_exact(self.uw, acc), self.gw_uC), f"{what}: g_w accumulators, u C"
+        assert np.array_equal(acc[self.orow].astype(np.int64), self.gw_acc_rows), f"{what}: g_w accumulator rows"
+        self.check_gw_output(gw_d, what)
+        assert_output_is_dequantised_accumulator(gw_d, acc_d, sgh_d, sx_d, self.n, what + " g_w")
+
+    def check_gw_output(self, gw_d, what):
+        got = gw_d.cpu().numpy()[self.orow]
+        assert_close_maxnorm(got, self.gw_rows, what + " g_w rows")
+        assert np.array_equal(got, dequant_fp32(self.gw_acc_rows, self.sh, self.sx, self.n)), \
+            f"{what}: g_w rows are not the fp32 dequantisation of the oracle's sums"
+
+
+def check_full_size_layer(hot, cfg, xd, wd, gyd, per_token, what, one_call_strategies=(0, 2)):
+    """One layer at its full size through every way the library computes it: the two separate
+    calls, then hot_linear_backward under each strategy given (0 = the library's own choice,
+    which is what the benchmark's sweeps time; 2 = the shared g_y passes wherever they exist).
+    Where the one-call form ran the shared passes, all its operands and both accumulators are
+    compared with the oracle again; where it ran the separate paths its outputs must be the
+    separate calls' bits.  Returns (g_x, g_w) of the default strategy."""
+    L, O = gyd.shape
+    I = wd.shape[1]
+    n, r = cfg.block, cfg.keep
+    _say(f"[full] {what} L={L} O={O} I={I} n={n} r={r} token={per_token}: oracle stages")
+    refs = FullSizeRefs(xd.cpu().numpy(), wd.cpu().numpy(), gyd.cpu().numpy(), n, r, per_token)
     ws = hot.alloc_workspace(cfg, L, O, I)
+    act = hot.alloc_act_buffer(cfg, L, I)
     q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
 
-    _say(f"[gx] {what} full L={L} O={O} I={I} n={n}")
-    qg_ref, sg_ref = oracle.quantize(oracle.transform_rows(gy, n), 4, per_token, oracle.PSEUDO_STOCHASTIC)
-    qw_ref, sw_ref = oracle.quantize(oracle.hla(w, n, n, np.arange(n)), 4, False, oracle.PSEUDO_STOCHASTIC)
+    _say(f"[full] {what}: separate calls")
     gx = torch.empty((L, I), device="cuda")
     hot.hot_linear_backward_gx(cfg, gyd, wd, q, gx, ws)
-    taps = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q)
+    t = hot.hot_debug_gx_operands(cfg, ws, L, O, I, q)
     torch.cuda.synchronize()
-    assert np.array_equal(taps["qg"].cpu().numpy(), qg_ref), f"{what}: g_y codes differ"
-    assert bits_equal(taps["sg"].cpu().numpy(), sg_ref), f"{what}: g_y scales differ"
-    assert np.array_equal(taps["qw"].cpu().numpy(), qw_ref), f"{what}: w codes differ"
-    assert bits_equal(taps["sw"].cpu().numpy(), sw_ref), f"{what}: w scale differs"
-    acc = taps["acc"].cpu().numpy()
-    del taps
-    v = rng.integers(-2048, 2048, size=I)
-    assert np.array_equal(_matvec_exact(acc, v), _matvec_exact(qg_ref, _matvec_exact(qw_ref, v)))
-    u = rng.integers(-2048, 2048, size=L)
-    assert np.array_equal(_vecmat_exact(u, acc), _vecmat_exact(_vecmat_exact(u, qg_ref), qw_ref))
-    rows = np.unique(np.concatenate([np.arange(0, 256), rng.integers(0, L, 512), np.arange(L - 200, L)]))
-    acc_rows, bad = oracle.igemm_nn(qg_ref[rows], qw_ref)
-    assert bad == 0 and np.array_equal(acc[rows].astype(np.int64), acc_rows)
-    ref_rows = oracle.dequant(acc_rows, sg_ref[rows] if per_token else sg_ref, sw_ref[0], n)
-    assert_close_maxnorm(gx[torch.from_numpy(rows).cuda()].cpu().numpy(), ref_rows, what + " g_x rows")
-    del acc, qg_ref, gx
-
-    _say(f"[gw] {what} full L={L} O={O} I={I} n={n} r={r}")
-    keep = oracle.lowpass_index(n, r)
-    xc_ref, sx_ref = oracle.compress_activation(x, n, r)
-    gh_ref, sh_ref = oracle.quantize(oracle.hla(gy, n, r, keep), 8, False, oracle.PSEUDO_STOCHASTIC)
-    act = hot.alloc_act_buffer(cfg, L, I)
+    refs.check_gx_operands(t["qg"], t["sg"], t["qw"], t["sw"], what)
+    refs.check_gx_product(t["acc"], gx, t["sg"], t["sw"], what)
+    del t
     hot.hot_compress_activation(cfg, xd, act, ws)
     codes, sx = hot.hot_debug_unpack_activation(cfg, act, L, I)
     gw = torch.empty((O, I), device="cuda")
     hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
-    taps = hot.hot_debug_gw_operands(cfg, ws, act, L, O, I)
+    t = hot.hot_debug_gw_operands(cfg, ws, act, L, O, I)
     torch.cuda.synchronize()
-    assert bits_equal(sx.cpu().numpy(), [sx_ref]) and np.array_equal(codes.cpu().numpy(), xc_ref), \
-        f"{what}: compressed activation differs"
-    assert bits_equal(taps["sg"].cpu().numpy(), sh_ref), f"{what}: HLA(g_y) scale differs"
-    assert np.array_equal(taps["qg"].cpu().numpy(), gh_ref), f"{what}: HLA(g_y) codes differ"
-    acc = taps["acc"].cpu().numpy()
-    v = rng.integers(-2048, 2048, size=I)
-    assert np.array_equal(_matvec_exact(acc, v), _vecmat_exact(_matvec_exact(xc_ref, v), gh_ref))
-    u = rng.integers(-2048, 2048, size=O)
-    assert np.array_equal(_vecmat_exact(u, acc), _vecmat_exact(_matvec_exact(gh_ref, u), xc_ref))
-    orow = np.unique(np.concatenate([np.arange(0, 64), rng.integers(0, O, 64), np.arange(O - 40, O)]))
-    acc_rows, bad = oracle.igemm_tn(np.ascontiguousarray(gh_ref[:, orow]), xc_ref)
-    assert bad == 0 and np.array_equal(acc[orow].astype(np.int64), acc_rows)
-    ref_rows = oracle.dequant(acc_rows, sh_ref, sx_ref, n)
-    assert_close_maxnorm(gw.cpu().numpy()[orow], ref_rows, what + " g_w rows")
+    refs.check_gw_operands(codes, sx, t["qg"], t["sg"], what)
+    refs.check_gw_product(t["acc"], gw, t["sg"], sx, what)
+    del t, codes
+
+    out = (gx, gw)
+    for strategy in one_call_strategies:
+        _say(f"[full] {what}: hot_linear_backward, strategy {strategy}")
+        gx1 = torch.full((L, I), float("nan"), device="cuda")
+        gw1 = torch.full((O, I), float("nan"), device="cuda")
+        ws.fill_(0x5A)
+        hot.hot_debug_set_backward_strategy(strategy)
+        try:
+            hot.hot_linear_backward(cfg, gyd, wd, act, q, gx1, gw1, ws)
+            try:
+                t = hot.hot_debug_fused_operands(cfg, ws, act, L, O, I, q)
+            except hot.HotError as e:       # this strategy ran the separate paths for this shape
+                assert e.status == hot.HOT_ERR_UNIMPLEMENTED
+                t = None
+        finally:
+            hot.hot_debug_set_backward_strategy(0)
+        torch.cuda.synchronize()
+        assert torch.equal(gx1, gx) and torch.equal(gw1, gw), f"{what}: strategy {strategy} differs from the separate calls"
+        if t is not None:
+            _say(f"[full] {what}: strategy {strategy} ran the shared g_y passes")
+            refs.check_gx_operands(t["qg"], t["sg"], t["qw"], t["sw"], what + " (shared passes)")
+            refs.check_gx_product(t["acc_gx"], gx1, t["sg"], t["sw"], what + " (shared passes)")
+            refs.check_gw_operands(None, None, t["qgh"], t["sgh"], what + " (shared passes)")
+            refs.check_gw_product(t["acc_gw"], gw1, t["sgh"], sx, what + " (shared passes)")
+        elif strategy == 0:
+            assert n != 16 or refs.gh.size * 4 <= 80e6, f"{what}: expected the shared passes by default"
+        if strategy == 0:
+            out = (gx1, gw1)
+        del t
+    return out
 
 
 @pytest.mark.parametrize("name,idx", [("cfg3_vitb_block_b256", 0), ("cfg3_vitb_block_b256", 1),
@@ -408,10 +521,87 @@ def check_full_size_sampled(hot, wl, layer, what, per_token=True):
                                       ("cfg5_vitl_chain", 0), ("cfg5_vitl_chain", 1)])
 def test_full_size_layers_sampled(name, idx):
     """Every layer of configs[2], [3] and [4] at its full token count (config 4: the 256x256
-    GEMM tiles and 64-row blocks; config 5: tensors beyond 2^31 bytes on either side)."""
+    GEMM tiles, 64-row blocks and the quantiser hot_select_quantizer picks at that size, which
+    must be the oracle's; config 5: tensors beyond 2^31 bytes on either side), through the
+    separate calls and through hot_linear_backward as the sweeps of the benchmark call it."""
     hot = _hot()
     wl = hot_inputs.WORKLOADS[name]
-    check_full_size_sampled(hot, wl, wl.layers[idx], f"{name}.{wl.layers[idx].name}")
+    layer = wl.layers[idx]
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    xd, wd, gyd = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
+    per_token = wl.quantizer == "token"
+    if wl.quantizer == "select":
+        ws = hot.alloc_workspace(cfg, layer.L, layer.O, layer.I)
+        choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, gyd, ws)
+        ref_choice, r_tok, r_ten = oracle.select_quantizer(gyd.cpu().numpy(), wl.block)
+        _say(f"[select] {name}.{layer.name} full size: {'token' if choice else 'tensor'} "
+             f"mse_token={m_tok:.6e} mse_tensor={m_ten:.6e} (oracle {r_tok:.6e} {r_ten:.6e})")
+        assert choice == int(ref_choice)
+        np.testing.assert_allclose([m_tok, m_ten], [r_tok, r_ten], rtol=1e-10)
+        per_token = bool(choice)
+        del ws
+    check_full_size_layer(hot, cfg, xd, wd, gyd, per_token, f"{name}.{layer.name}")
+
+
+@pytest.mark.parametrize("name,idx", [("cfg3_vitb_block_b256", 1), ("cfg5_vitl_chain", 1), ("cfg4_llm7b_mlp", 1)])
+def test_full_size_layers_per_tensor_quantiser(name, idx):
+    """The other outcome of the quantiser selection at full size: one scale for the whole
+    rotated g_y (one more pass over g_y on the separate path, a tensor-wide maximum in the
+    shared passes)."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS[name]
+    layer = wl.layers[idx]
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    xd, wd, gyd = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
+    check_full_size_layer(hot, cfg, xd, wd, gyd, False, f"{name}.{layer.name} per-tensor")
+
+
+def test_config5_chain_slice_at_full_size():
+    """Three consecutive layers from the top of the ViT-L chain at 201728 tokens, as the
+    benchmark's sweep runs them: each layer's g_x (as the GPU produced it) is the g_y of the
+    layer below, and the oracle's stages of that layer are computed from exactly those bits."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg5_vitl_chain"]
+    cfg = hot.Config(block=wl.block, keep=wl.keep)
+    fc1, fc2 = wl.layers
+    depth = int(wl.extra["depth"])
+    gyd = None
+    for name, layer in ((f"{depth - 1}.fc2", fc2), (f"{depth - 1}.fc1", fc1), (f"{depth - 2}.fc2", fc2)):
+        tag = f"{wl.name}.{name}"
+        xd = hot_inputs.make_x(wl.x_kind, layer.L, layer.I, 0, tag, "cuda")
+        wd = hot_inputs.make_w(layer.O, layer.I, 0, tag, "cuda")
+        if gyd is None:
+            gyd = hot_inputs.make_gy(wl.gy_kind, layer.L, layer.O, 0, tag, "cuda")
+        assert tuple(gyd.shape) == (layer.L, layer.O)
+        gx, gw = check_full_size_layer(hot, cfg, xd, wd, gyd, True, tag, one_call_strategies=(0,))
+        assert torch.isfinite(gx).all().item() and gx.abs().max().item() > 0
+        del xd, wd
+        gyd = gx
+
+
+def test_config2_per_sample_tiling_at_full_size():
+    """configs[1] with its 64 samples of 197 tokens tiled separately (12 blocks of 16 and a
+    padded one of 5 per sample would be n = 16; here n = 32: 6 blocks and one of 5 tokens), as
+    `bench.py --sample-tokens 197` times it: INT8 and bfloat16 g_w operands, every element."""
+    hot = _hot()
+    wl = hot_inputs.WORKLOADS["cfg2_vitb_fc1"]
+    x, w, gy = hot_inputs.make_layer(wl, wl.layers[0], seed=0)
+    cfg = hot.Config(block=wl.block, keep=wl.keep, sample_tokens=197)
+    ref, gw = check_gw(hot, cfg, gy, x, "cfg2 per-sample")
+    check_gw_bf16(hot, hot.Config(block=wl.block, keep=wl.keep, sample_tokens=197, gw_bits=16), gy, x,
+                  "cfg2 per-sample bf16")
+    # the one-call form, as the benchmark calls it
+    L, O = gy.shape
+    I = w.shape[1]
+    ws = hot.alloc_workspace(cfg, L, O, I)
+    act = hot.alloc_act_buffer(cfg, L, I)
+    gx1, gw1 = torch.empty((L, I), device="cuda"), torch.empty((O, I), device="cuda")
+    hot.hot_compress_activation(cfg, x.cuda(), act, ws)
+    hot.hot_linear_backward(cfg, gy.cuda(), w.cuda(), act, hot.HOT_Q_PER_TOKEN, gx1, gw1, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gw1, gw)
+    ref_x = oracle.backward_gx(gy.numpy(), w.numpy(), wl.block, per_token=True)
+    assert_close_maxnorm(gx1.cpu().numpy(), ref_x["g_x"], "cfg2 per-sample one call g_x")
 
 
 # ---- one-call backward: both gradients from shared reads of g_y --------------------
