@@ -1,10 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the HOT linear-layer backward hot path on one MI355X.
 
-One step = one pass of the whole path over one batch of synthetic input:
-forward-time activation compression, the g_x path and the g_w path of one
-linear layer (Sec. 5.1, 5.2, 5.2.1).  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line.
+One step = one pass of the whole path over one batch of synthetic input: forward-time
+activation compression of every layer of a workload (Sec. 5.2.1), then the g_x and g_w
+paths of every layer (Sec. 5.1, 5.2), top layer first; in a chain each layer's g_x is the
+g_y of the layer below.  All inputs are resident in HBM before the timed region.
+
+With no --workload the headline is the largest single-GPU workload (the ViT-L chain at
+201728 tokens, 48 layers per step) and the four smaller configurations are run the same
+way and reported under "workloads".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -21,54 +25,258 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA
 BF16_PEAK_TOPS = 2500.0     # MI355X dense bf16 MFMA (gw_bits = 16 variant)
+HEADLINE = "cfg5_vitl_chain"
+OTHERS = ["cfg1_single_512x768x768", "cfg2_vitb_fc1", "cfg3_vitb_block_b256", "cfg4_llm7b_mlp"]
+STRATEGY = {"auto": 0, "separate": 1, "shared": 2, "unfused": 3}
 
 
 def stage_model(L, O, I, n, r, gx_bits, per_token, gw_bits=8, Lr=None):
     """Algorithmic work per launch of every kernel role: HBM bytes for the
-    transform/quantise kernels, integer ops (and compulsory bytes) for the GEMMs."""
+    transform/quantise kernels, operations and compulsory bytes for the GEMMs."""
     Lr = L // n * r if Lr is None else Lr
     cb = gx_bits / 8.0
     wb = gw_bits / 8.0
-    m = {
-        "act_col_absmax": dict(bound="hbm", bytes=4 * L * I),
-        "act_col_quant": dict(bound="hbm", bytes=4 * L * I + wb * Lr * I),
-        "w_col_absmax": dict(bound="hbm", bytes=4 * O * I),
-        "w_col_quant": dict(bound="hbm", bytes=4 * O * I + cb * O * I),
-        "gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L),
-        "w_and_gy_row_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + 4 * L + 4 * O * I + cb * O * I),
-        "gy_row_absmax": dict(bound="hbm", bytes=4 * L * O),
-        "gy_row_quant2": dict(bound="hbm", bytes=4 * L * O + cb * L * O),
-        "gyT_col_absmax": dict(bound="hbm", bytes=4 * L * O),
-        "gyT_col_quant": dict(bound="hbm", bytes=4 * L * O + wb * Lr * O),
-        "gy_fused_absmax": dict(bound="hbm", bytes=4 * L * O + (4 * L * ((O + 127) // 128) if per_token else 0)),
-        "gy_fused_quant": dict(bound="hbm", bytes=4 * L * O + cb * L * O + Lr * O + 4 * L),
-        "gx_igemm": dict(bound="mfma", ops=2 * L * O * I, bytes=cb * (L * O + I * O) + 4 * L * I),
-        "gw_igemm": dict(bound="mfma", ops=2 * O * I * Lr, bytes=wb * Lr * (O + I) + 4 * O * I,
+    return {
+        "act_col_absmax": dict(bytes=4 * L * I),
+        "act_col_quant": dict(bytes=4 * L * I + wb * Lr * I),
+        "w_col_absmax": dict(bytes=4 * O * I),
+        "w_col_quant": dict(bytes=4 * O * I + cb * O * I),
+        "gy_row_quant": dict(bytes=4 * L * O + cb * L * O + 4 * L),
+        "w_and_gy_row_quant": dict(bytes=4 * L * O + cb * L * O + 4 * L + 4 * O * I + cb * O * I),
+        "gy_row_absmax": dict(bytes=4 * L * O),
+        "gy_row_quant2": dict(bytes=4 * L * O + cb * L * O),
+        "gyT_col_absmax": dict(bytes=4 * L * O),
+        "gyT_col_quant": dict(bytes=4 * L * O + wb * Lr * O),
+        "gy_fused_absmax": dict(bytes=4 * L * O + (4 * L * ((O + 127) // 128) if per_token else 0)),
+        "gy_fused_quant": dict(bytes=4 * L * O + cb * L * O + Lr * O + 4 * L),
+        "gx_igemm": dict(ops=2 * L * O * I, bytes=cb * (L * O + I * O) + 4 * L * I, peak=INT8_PEAK_TOPS),
+        "gw_igemm": dict(ops=2 * O * I * Lr, bytes=wb * Lr * (O + I) + 4 * O * I,
                          peak=BF16_PEAK_TOPS if gw_bits == 16 else INT8_PEAK_TOPS),
     }
-    return m
 
 
-def profiled_traffic(workload, role):
-    """HBM bytes per launch (fetched + written) of a kernel role, from the committed
-    rocprofv3 counter summary of this workload (FETCH_SIZE / WRITE_SIZE, scaled by a copy
-    of known size); None when no summary covers it."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic_{workload}.txt")
+def kernel_entry(mdl, avg_us, launches_per_step):
+    """One row of the per-kernel table.  A transform kernel is priced against the HBM peak.
+    A GEMM is priced against whichever of its two lower bounds is the larger: operations at
+    the matrix peak of its operand type, or compulsory bytes (operands once, output once) at
+    the HBM peak: the g_x GEMM of a layer with few output features writes more fp32 output
+    than its operations can cover."""
+    k = dict(avg_us=round(avg_us, 3), launches_per_step=launches_per_step)
+    if not mdl:
+        return k
+    t = avg_us * 1e-6
+    k["GBps"] = round(mdl["bytes"] / t / 1e9, 1)
+    if "ops" in mdl:
+        k["TOPS"] = round(mdl["ops"] / t / 1e12, 2)
+        t_mfma = mdl["ops"] / (mdl["peak"] * 1e12)
+        t_hbm = mdl["bytes"] / (HBM_PEAK_GBS * 1e9)
+        k["bound"] = "mfma" if t_mfma >= t_hbm else "hbm"
+        k["frac"] = round(max(t_mfma, t_hbm) / t, 4)
+        k["frac_mfma"] = round(t_mfma / t, 4)
+        k["peak_TOPS"] = mdl["peak"]
+    else:
+        k["bound"] = "hbm"
+        k["frac"] = round(k["GBps"] / HBM_PEAK_GBS, 4)
+    return k
+
+
+def profiled_traffic(workload, key):
+    """HBM bytes per launch (fetched + written) of a kernel, from the committed rocprofv3
+    counter summary of this workload (FETCH_SIZE / WRITE_SIZE runs, scaled by a copy of known
+    size); (None, None) when no summary covers it."""
+    rel = os.path.join("profiles", f"hbm_traffic_{workload}.txt")
     try:
-        with open(path) as fh:
+        with open(os.path.join(ROOT, rel)) as fh:
             for line in fh:
                 f = line.split()
-                if len(f) == 4 and f[0] == "traffic_bytes" and f[1] == role:
-                    return int(f[2]) + int(f[3])
+                if len(f) == 4 and f[0] == "traffic_bytes" and f[1] == key:
+                    return int(f[2]) + int(f[3]), rel
     except OSError:
         pass
-    return None
+    return None, None
+
+
+class Job:
+    """One workload with everything a step needs resident on the device."""
+
+    def __init__(self, torch, hot, hot_inputs, wl, args):
+        self.torch, self.hot, self.wl = torch, hot, wl
+        n, r = wl.block, wl.keep
+        self.cfg = hot.Config(block=n, keep=r, gw_bits=args.gw_bits, sample_tokens=args.sample_tokens)
+        depth = int(wl.extra.get("depth", 0))
+        self.chain = depth > 0
+        self.layers = [(f"{d}.{l.name}", l) for d in range(depth) for l in wl.layers] if self.chain \
+            else [(l.name, l) for l in wl.layers]
+        cfg = self.cfg
+        self.ws = torch.empty(max(hot.hot_workspace_bytes(cfg, l.L, l.O, l.I) for _, l in self.layers),
+                              dtype=torch.uint8, device="cuda")
+        self.x, self.w, self.gy, self.act, self.gx, self.gw, self.quant = [], [], [], [], [], [], []
+        shared_out = {}
+        for k, (name, l) in enumerate(self.layers):
+            tag = f"{wl.name}.{name}"
+            self.x.append(hot_inputs.make_x(wl.x_kind, l.L, l.I, 0, tag, "cuda"))
+            self.w.append(hot_inputs.make_w(l.O, l.I, 0, tag, "cuda"))
+            top = k == len(self.layers) - 1
+            self.gy.append(hot_inputs.make_gy(wl.gy_kind, l.L, l.O, 0, tag, "cuda")
+                           if (top or not self.chain) else None)
+            self.act.append(hot.alloc_act_buffer(cfg, l.L, l.I))
+            # outputs of layers of one shape share a buffer in a chain (a g_x is consumed by the
+            # next call and nothing else), otherwise each layer has its own
+            key = (l.L, l.O, l.I) if self.chain else k
+            if key not in shared_out:
+                shared_out[key] = (torch.empty((l.L, l.I), device="cuda"), torch.empty((l.O, l.I), device="cuda"))
+            self.gx.append(shared_out[key][0])
+            self.gw.append(shared_out[key][1])
+            self.quant.append(args.quantizer or wl.quantizer)
+        self.selected = {}
+        for k, (name, l) in enumerate(self.layers):     # calibration, before training (Sec. 5.2.2)
+            if self.quant[k] == "select":
+                choice, m_tok, m_ten = hot.hot_select_quantizer(cfg, self.gy[k], self.ws)
+                self.quant[k] = "token" if choice == hot.HOT_Q_PER_TOKEN else "tensor"
+                self.selected[name] = dict(choice=self.quant[k], mse_token=m_tok, mse_tensor=m_ten)
+        self.q = [hot.HOT_Q_PER_TOKEN if q == "token" else hot.HOT_Q_PER_TENSOR for q in self.quant]
+        self.stream = torch.cuda.current_stream()
+        self.ops = sum(2.0 * l.L * l.O * l.I + 2.0 * l.O * l.I * cfg.reduced_tokens(l.L) for _, l in self.layers)
+        self.act_bytes = sum(a.numel() for a in self.act)
+        self.fp32_bytes = sum(4 * l.L * l.I for _, l in self.layers)
+
+    def compress(self, k):
+        self.hot.hot_compress_activation(self.cfg, self.x[k], self.act[k], self.ws, stream=self.stream)
+
+    def backward(self, k):
+        g_y = self.gy[k] if self.gy[k] is not None else self.gx[k + 1]
+        self.hot.hot_linear_backward(self.cfg, g_y, self.w[k], self.act[k], self.q[k], self.gx[k], self.gw[k],
+                                     self.ws, stream=self.stream)
+
+    def step(self):
+        for k in range(len(self.layers)):
+            self.compress(k)
+        for k in range(len(self.layers) - 1, -1, -1):
+            self.backward(k)
+
+    def timed(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def kernel_table(self, steps):
+        """The same steps with HIP events around every kernel (recorded on the launch stream),
+        one layer call at a time; kernels are keyed "<layer>.<role>", layers of a chain that
+        share a shape pooled under the layer's name."""
+        hot, cfg = self.hot, self.cfg
+        acc = {}
+
+        def take(lname, prof):
+            for role, (ms, cnt) in prof.items():
+                a = acc.setdefault((lname, role), [0.0, 0])
+                a[0] += ms
+                a[1] += cnt
+
+        for _ in range(steps):
+            for k, (name, l) in enumerate(self.layers):
+                hot.hot_debug_profile_begin()
+                self.compress(k)
+                take(name.split(".")[-1], hot.hot_debug_profile_end())
+            for k in range(len(self.layers) - 1, -1, -1):
+                hot.hot_debug_profile_begin()
+                self.backward(k)
+                take(self.layers[k][0].split(".")[-1], hot.hot_debug_profile_end())
+        shapes = {name.split(".")[-1]: (l, self.quant[k]) for k, (name, l) in enumerate(self.layers)}
+        table = {}
+        for (lname, role), (ms, cnt) in acc.items():
+            l, quant = shapes[lname]
+            mdl = stage_model(l.L, l.O, l.I, cfg.block, cfg.keep, cfg.gx_bits, quant == "token", cfg.gw_bits,
+                              cfg.reduced_tokens(l.L)).get(role)
+            e = kernel_entry(mdl, ms * 1e3 / cnt, cnt / steps)
+            e["step_us"] = round(ms * 1e3 / steps, 1)
+            if mdl:
+                e["algorithmic_bytes"] = int(mdl["bytes"])
+                if "ops" in mdl:
+                    e["algorithmic_ops"] = int(mdl["ops"])
+            table[f"{lname}.{role}"] = e
+        return table
+
+    def layer_table(self):
+        """Per-layer times of one more step (HIP events around each call) and output sanity."""
+        torch = self.torch
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        rows = {}
+        marks = []
+        for k in range(len(self.layers)):
+            e0, e1 = ev(), ev()
+            e0.record()
+            self.compress(k)
+            e1.record()
+            marks.append((k, "compress_us", e0, e1))
+        for k in range(len(self.layers) - 1, -1, -1):
+            e0, e1 = ev(), ev()
+            e0.record()
+            self.backward(k)
+            e1.record()
+            marks.append((k, "backward_us", e0, e1))
+        torch.cuda.synchronize()
+        for k, what, e0, e1 in marks:
+            lname = self.layers[k][0].split(".")[-1]
+            row = rows.setdefault(lname, dict(layers=0, compress_us=0.0, backward_us=0.0))
+            row[what] += e0.elapsed_time(e1) * 1e3
+            if what == "compress_us":
+                row["layers"] += 1
+        out = {}
+        for lname, row in rows.items():
+            l = next(l for name, l in self.layers if name.split(".")[-1] == lname)
+            quant = next(self.quant[k] for k, (name, _) in enumerate(self.layers) if name.split(".")[-1] == lname)
+            ops = 2.0 * l.L * l.O * l.I + 2.0 * l.O * l.I * self.cfg.reduced_tokens(l.L)
+            bw = row["backward_us"] / row["layers"]
+            out[lname] = dict(L=l.L, O=l.O, I=l.I, layers=row["layers"], gy_quantizer=quant,
+                              compress_us=round(row["compress_us"] / row["layers"], 1),
+                              backward_us=round(bw, 1), backward_TOPS=round(ops / bw / 1e6, 1))
+        finite = all(bool(torch.isfinite(t).all().item()) for t in set(self.gx) | set(self.gw))
+        return out, finite
+
+
+def summarise(job, ms_per_step, table, layers, finite, torch):
+    cfg, wl = job.cfg, job.wl
+    out = dict(workload=wl.name, layers_per_step=len(job.layers), us_per_step=round(ms_per_step * 1e3, 2),
+               effective_TOPS=round(job.ops / (ms_per_step * 1e-3) / 1e12, 2),
+               block=cfg.block, keep=cfg.keep, gx_bits=cfg.gx_bits, gw_bits=cfg.gw_bits,
+               act_buffer_bytes=job.act_bytes, act_fp32_bytes=job.fp32_bytes,
+               act_ratio=round(job.act_bytes / job.fp32_bytes, 4),
+               peak_device_bytes=int(torch.cuda.max_memory_allocated()),
+               outputs_finite=finite, layers=layers, kernels=table)
+    if job.selected:
+        out["select_quantizer"] = job.selected
+    return out
+
+
+def pick_roofline(workload, table):
+    """The kernel the roofline object describes: among the kernels whose average launch is
+    within 10 % of the longest one, the one with the lowest fraction of its bound."""
+    priced = {k: v for k, v in table.items() if "frac" in v}
+    longest = max(v["avg_us"] for v in priced.values())
+    key = min((k for k, v in priced.items() if v["avg_us"] >= 0.9 * longest), key=lambda k: priced[k]["frac"])
+    d = priced[key]
+    traffic, source = profiled_traffic(workload, key)
+    if d["bound"] == "hbm":
+        roof = dict(kernel=key, bound="hbm", achieved=d["GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=d["frac"], traffic=traffic, algorithmic_bytes=d["algorithmic_bytes"], avg_us=d["avg_us"])
+    else:
+        roof = dict(kernel=key, bound="mfma", achieved=d["TOPS"], peak=d["peak_TOPS"], unit="TOP/s",
+                    frac=d["frac"], traffic=traffic, algorithmic_ops=d["algorithmic_ops"], avg_us=d["avg_us"])
+    if traffic is not None:
+        roof["traffic_source"] = f"{source} (rocprofv3 counter runs of an earlier session, not of this run)"
+    return roof
 
 
 def run_sweep(torch, hot, hot_inputs, wl, quantizer_flag):
-    """Forward-time compression of every layer of a workload, then the backward of every
-    layer (a chain when the workload says so: each g_x is the next lower layer's g_y).
-    Returns per-layer times (HIP events on the launch stream), buffer bytes and peak memory."""
+    """Streamed form of one step, for the peak-memory figure: inputs are generated layer by
+    layer and only what the backward needs (the compressed activations) is kept.
+    Returns per-layer times (HIP events), buffer bytes and peak memory."""
     n, r = wl.block, wl.keep
     cfg = hot.Config(block=n, keep=r)
     depth = int(wl.extra.get("depth", 0))
@@ -159,19 +367,81 @@ def probe_peaks(torch, hot):
     return out
 
 
+def cpu_baseline(job, seconds, sample_tokens):
+    """The oracle, as it stands, on a bounded sample of the workload: the first tokens of one
+    layer of every shape (compress + g_x + g_w), repeated for about `seconds` of wall time."""
+    import oracle
+    oracle.lib()
+    cfg, n, r = job.cfg, job.cfg.block, job.cfg.keep
+    seen, sample = set(), []
+    for k in range(len(job.layers) - 1, -1, -1):
+        name, l = job.layers[k]
+        if (l.O, l.I) in seen:
+            continue
+        seen.add((l.O, l.I))
+        if cfg.sample_tokens:     # the oracle's per-sample definition: zero tokens after every sample
+            Ls = l.L
+        else:
+            Ls = l.L if sample_tokens <= 0 else min(l.L, max(n, sample_tokens // n * n))
+        gy = job.gy[k] if job.gy[k] is not None else job.gx[k + 1]
+        sample.append((name, l, Ls, job.x[k][:Ls].cpu().numpy(), gy[:Ls].cpu().numpy(), job.w[k].cpu().numpy(),
+                       job.quant[k] == "token"))
+    reps, dt, ops = 0, 0.0, 0.0
+    while reps < 1 or (dt < seconds and reps < 64):
+        t0 = time.perf_counter()
+        for name, l, Ls, xs, gys, wh, per_token in sample:
+            oracle.backward_gx(gys, wh, n, bits=cfg.gx_bits, per_token=per_token, taps=False)
+            if cfg.sample_tokens:
+                xs_t, gys_t = oracle.pad_samples(xs, cfg.sample_tokens, n), oracle.pad_samples(gys, cfg.sample_tokens, n)
+            else:
+                xs_t, gys_t = xs, gys
+            if cfg.gw_bits == 16:
+                oracle.backward_gw_bf16(gys_t, oracle.compress_activation_bf16(xs_t, n, r), n, r)
+            else:
+                codes, sx = oracle.compress_activation(xs_t, n, r)
+                oracle.backward_gw(gys_t, codes, sx, n, r, taps=False)
+        dt += time.perf_counter() - t0
+        reps += 1
+    ops = sum(2.0 * Ls * l.O * l.I + 2.0 * l.O * l.I * cfg.reduced_tokens(Ls) for _, l, Ls, *_ in sample)
+    what = ", ".join(f"{'all' if Ls == l.L else 'first ' + str(Ls) + ' of'} {l.L} tokens of {name} ({l.O}x{l.I})"
+                     for name, l, Ls, *_ in sample)
+    return dict(value=round(ops * reps / dt / 1e12, 6), unit="TOPS", cores=oracle.threads(), kind="oracle",
+                sample=f"{job.wl.name}: {what}; compress + g_x + g_w of each, {reps} passes in {dt:.1f} s; the "
+                       f"oracle's rate on the sample stands for its rate on the whole step (cost is linear in tokens)",
+                seconds_per_pass=round(dt / reps, 3))
+
+
+def run_job(torch, hot, hot_inputs, wl, args, want_cpu):
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    job = Job(torch, hot, hot_inputs, wl, args)
+    ms = job.timed(args.steps, args.warmup)
+    table = job.kernel_table(max(1, min(args.steps, 5 if len(job.layers) > 8 else 20)))
+    layers, finite = job.layer_table()
+    res = summarise(job, ms, table, layers, finite, torch)
+    cpu = None
+    if want_cpu:
+        cpu = cpu_baseline(job, args.cpu_seconds, args.cpu_sample_tokens or (16384 if len(job.layers) > 1 else 0))
+    del job
+    return res, ms, cpu
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2_vitb_fc1")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None,
+                    help="run this workload only (default: the ViT-L chain as the headline and the four "
+                         "smaller configurations under 'workloads')")
     ap.add_argument("--quantizer", default=None, choices=[None, "token", "tensor"])
     ap.add_argument("--cpu-sample-tokens", type=int, default=0,
-                    help="tokens of the workload the oracle is timed on (0 = all of them)")
+                    help="tokens per layer the oracle is timed on (0 = 16384 for multi-layer workloads, "
+                         "all tokens for single layers)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="repeat the oracle on the sample until about this much CPU wall time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--backward", default="auto", choices=["auto", "separate", "shared", "unfused"],
+    ap.add_argument("--backward", default="auto", choices=list(STRATEGY),
                     help="how hot_linear_backward produces the two views of g_y: the library's "
                          "choice (default), always the two separate paths, or the shared g_y "
                          "passes wherever they exist")
@@ -187,11 +457,10 @@ def main() -> int:
                     help="tile the token axis per sample of this many tokens (197 for the ViT "
                          "workloads) instead of as one run")
     ap.add_argument("--sweep", action="store_true",
-                    help="instead of the timed step, run every layer of the workload once (compress "
-                         "all, then backward all; chained where the workload is a chain) and print "
-                         "per-layer times, buffer bytes and peak device memory as JSON")
+                    help="instead of the timed steps, run the streamed form of one step (inputs generated "
+                         "layer by layer) and print per-layer times, buffer bytes and peak memory as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain device copy of g_y (for scaling rocprofv3 byte counters)")
+                    help="also run a plain device copy of 154.9 MB (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build runs the HOT backward on ONE GPU; "
@@ -207,131 +476,60 @@ def main() -> int:
     if args.probe_peaks:
         print(json.dumps(probe_peaks(torch, hot)))
         return 0
-    wl = hot_inputs.WORKLOADS[args.workload]
     hot.hot_debug_set_gemm_mode(args.gemm)
+    hot.hot_debug_set_backward_strategy(STRATEGY[args.backward])
     if args.sweep:
-        hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2, "unfused": 3}[args.backward])
+        wl = hot_inputs.WORKLOADS[args.workload or HEADLINE]
         run_sweep(torch, hot, hot_inputs, wl, args.quantizer)   # warm-up: code objects, allocator
         print(json.dumps(run_sweep(torch, hot, hot_inputs, wl, args.quantizer)))
         return 0
-    layer = wl.layers[0]
-    L, O, I, n, r = layer.L, layer.O, layer.I, wl.block, wl.keep
-    quant = args.quantizer or ("token" if wl.quantizer in ("token", "select") else "tensor")
-    per_token = quant == "token"
-    cfg = hot.Config(block=n, keep=r, gw_bits=args.gw_bits, sample_tokens=args.sample_tokens)
-
-    x, w, gy = hot_inputs.make_layer(wl, layer, seed=0, device="cuda")
-    ws = hot.alloc_workspace(cfg, L, O, I)
-    act = hot.alloc_act_buffer(cfg, L, I)
-    gx = torch.empty((L, I), device="cuda")
-    gw = torch.empty((O, I), device="cuda")
-    q = hot.HOT_Q_PER_TOKEN if per_token else hot.HOT_Q_PER_TENSOR
-    stream = torch.cuda.current_stream()
-    hot.hot_debug_set_backward_strategy({"auto": 0, "separate": 1, "shared": 2, "unfused": 3}[args.backward])
-
-    def step():
-        hot.hot_compress_activation(cfg, x, act, ws, stream=stream)
-        hot.hot_linear_backward(cfg, gy, w, act, q, gx, gw, ws, stream=stream)
-
     if args.calibrate_copy:
-        scratch = torch.empty_like(gy)
+        a = torch.empty(12608 * 3072, device="cuda")
+        b = torch.empty_like(a)
         for _ in range(5):
-            scratch.copy_(gy)
+            b.copy_(a)
         torch.cuda.synchronize()
-        del scratch
+        del a, b
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    head_wl = hot_inputs.WORKLOADS[args.workload or HEADLINE]
+    others = {}
+    streamed_peak = None
+    if args.workload is None:
+        # the peak-memory figure of the headline: a streamed step, before its inputs are made resident
+        streamed_peak = run_sweep(torch, hot, hot_inputs, head_wl, args.quantizer)["peak_device_bytes"]
+        for name in OTHERS:
+            res, _, _ = run_job(torch, hot, hot_inputs, hot_inputs.WORKLOADS[name], args, False)
+            others[name] = res
+    head, ms_per_step, cpu = run_job(torch, hot, hot_inputs, head_wl, args, not args.no_cpu_baseline)
+    roof = pick_roofline(head_wl.name, head["kernels"])
 
-    # same steps again with HIP events around every kernel (on the launch stream)
-    hot.hot_debug_profile_begin()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof = hot.hot_debug_profile_end()
-
-    model = stage_model(L, O, I, n, r, cfg.gx_bits, per_token, cfg.gw_bits, cfg.reduced_tokens(L))
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        avg_us = ms * 1e3 / cnt
-        k = dict(avg_us=round(avg_us, 3), launches_per_step=cnt / args.steps)
-        mdl = model.get(name)
-        if mdl:
-            k["bound"] = mdl["bound"]
-            k["GBps"] = round(mdl["bytes"] / (avg_us * 1e-6) / 1e9, 1)
-            if "ops" in mdl:
-                k["TOPS"] = round(mdl["ops"] / (avg_us * 1e-6) / 1e12, 2)
-            # fraction of the published peak that bounds this kernel (HBM 8 TB/s or the MFMA peak)
-            k["frac"] = round(k["TOPS"] / mdl.get("peak", INT8_PEAK_TOPS) if mdl["bound"] == "mfma"
-                              else k["GBps"] / HBM_PEAK_GBS, 4)
-        kernels[name] = k
-    dominant = max((k for k in kernels if k in model), key=lambda k: kernels[k]["avg_us"])
-    d, dm = kernels[dominant], model[dominant]
-    if dm["bound"] == "hbm":
-        roof = dict(kernel=dominant, bound="hbm", achieved=d["GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(d["GBps"] / HBM_PEAK_GBS, 4), traffic=None,
-                    algorithmic_bytes=int(dm["bytes"]), avg_us=d["avg_us"])
-    else:
-        peak = dm.get("peak", INT8_PEAK_TOPS)
-        roof = dict(kernel=dominant, bound="mfma", achieved=d["TOPS"], peak=peak, unit="TOP/s",
-                    frac=round(d["TOPS"] / peak, 4), traffic=None,
-                    algorithmic_ops=int(dm["ops"]), avg_us=d["avg_us"])
-
-    if quant == "token" and args.backward == "auto" and args.gw_bits == 8 and not args.sample_tokens:   # what the counter runs measured
-        roof["traffic"] = profiled_traffic(wl.name, dominant)
-    Lr = cfg.reduced_tokens(L)
-    ops_step = 2 * L * O * I + 2 * O * I * Lr          # integer ops actually executed
-    value = ops_step / (ms_per_step * 1e-3) / 1e12
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        Ls = L if args.cpu_sample_tokens <= 0 else min(L, max(n, args.cpu_sample_tokens // n * n))
-        xs, gys, wh = x[:Ls].cpu().numpy(), gy[:Ls].cpu().numpy(), w.cpu().numpy()
-        oracle.lib()
-        if cfg.sample_tokens:     # the oracle's per-sample definition: zero tokens after every sample
-            Ls = L
-            xs, gys = x.cpu().numpy(), gy.cpu().numpy()
-            xs_t, gys_t = oracle.pad_samples(xs, cfg.sample_tokens, n), oracle.pad_samples(gys, cfg.sample_tokens, n)
-        else:
-            xs_t, gys_t = xs, gys
-        reps, dt = 0, 0.0
-        while reps < 1 or (dt < args.cpu_seconds and reps < 64):
-            t0 = time.perf_counter()
-            oracle.backward_gx(gys, wh, n, bits=cfg.gx_bits, per_token=per_token, taps=False)
-            if cfg.gw_bits == 16:
-                oracle.backward_gw_bf16(gys_t, oracle.compress_activation_bf16(xs_t, n, r), n, r)
-            else:
-                codes, sx = oracle.compress_activation(xs_t, n, r)
-                oracle.backward_gw(gys_t, codes, sx, n, r, taps=False)
-            dt += time.perf_counter() - t0
-            reps += 1
-        ops_s = 2 * Ls * O * I + 2 * O * I * cfg.reduced_tokens(Ls)
-        cpu = dict(value=round(ops_s * reps / dt / 1e12, 6), unit="TOPS", cores=oracle.threads(), kind="oracle",
-                   sample=f"{'all' if Ls == L else 'first ' + str(Ls) + ' of'} {L} tokens of {wl.name} "
-                          f"(compress + g_x + g_w), {reps} passes in {dt:.1f} s",
-                   seconds_per_pass=round(dt / reps, 3))
-
+    cfg = hot.Config(block=head_wl.block, keep=head_wl.keep, gw_bits=args.gw_bits, sample_tokens=args.sample_tokens)
     out = {
         "metric": "HOT linear-backward effective TOPS (integer ops executed / step time)",
-        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8" if cfg.gw_bits == 8 else "int8 (g_x) + bf16 (g_w)",
+        "value": head["effective_TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "us_per_step": head["us_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8" if cfg.gw_bits == 8 else "int8 (g_x) + bf16 (g_w)",
         "data": "synthetic",
-        "config": {"workload": wl.name, "L": L, "O": O, "I": I, "block": n, "keep": r,
-                   "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits, "gy_quantizer": quant,
+        "config": {"workload": head_wl.name, "layers_per_step": head["layers_per_step"],
+                   "layers": {k: [v["L"], v["O"], v["I"]] for k, v in head["layers"].items()},
+                   "block": cfg.block, "keep": cfg.keep, "gx_bits": cfg.gx_bits, "gw_bits": cfg.gw_bits,
+                   "gy_quantizer": {k: v["gy_quantizer"] for k, v in head["layers"].items()},
                    "sample_tokens": cfg.sample_tokens,
-                   "step": "compress_activation + linear_backward (g_x and g_w; g_y views: %s; GEMM work "
-                           "distribution: %s)" % (args.backward, {0: "auto", 1: "tile"}.get(args.gemm, "K split %d" % args.gemm))},
-        "act_buffer_bytes": hot.hot_act_buffer_bytes(cfg, L, I), "act_fp32_bytes": 4 * L * I,
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+                   "step": "compress_activation of every layer, then linear_backward (g_x and g_w) of every layer, "
+                           "top first%s; g_y views: %s; GEMM work distribution: %s"
+                           % (" (each g_x is the next g_y)" if head_wl.extra.get("depth") else "", args.backward,
+                              {0: "auto", 1: "tile"}.get(args.gemm, "K split %d" % args.gemm))},
+        "act_buffer_bytes": head["act_buffer_bytes"], "act_fp32_bytes": head["act_fp32_bytes"],
+        "peak_device_bytes": head["peak_device_bytes"],
+        "peak_device_bytes_streamed": streamed_peak,
+        "outputs_finite": head["outputs_finite"],
+        "roofline": roof, "cpu_baseline": cpu, "layers": head["layers"], "kernels": head["kernels"],
     }
+    if "select_quantizer" in head:
+        out["select_quantizer"] = head["select_quantizer"]
+    if others:
+        out["workloads"] = others
     print(json.dumps(out))
     return 0
 
