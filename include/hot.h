@@ -263,8 +263,10 @@ hot_status hot_debug_set_exchange_wait_us(int us);
  * outputs with no more tiles than compute units), 1 = one workgroup per output tile,
  * s = 2..8: the K range cut into s slices, one workgroup each, wherever a split of the
  * 128x128 tile applies (integer operands, at least 4 K stages per slice); the slices'
- * partial sums are handed to the last one through the workspace.  Integer results, and
- * therefore all outputs, do not depend on it.  Process-wide. */
+ * partial sums are handed to the last one through the workspace; 10 / 11 / 12 / 13: every
+ * GEMM on 128x128 / 192x256 / 256x256 / 128x256 tiles, one workgroup per tile (11 and 13
+ * exist for INT4 operands only; INT8 and bfloat16 GEMMs then take 256x256).  Integer results, and therefore all outputs, do not depend on it.
+ * Process-wide. */
 hot_status hot_debug_set_gemm_mode(int mode);
 
 /* ---- stage timing for benchmarks (off by default) ---- */

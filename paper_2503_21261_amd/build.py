@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import shlex
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -35,13 +36,16 @@ def _hipcc() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every .hip source and link libhot.so.  Always recompiles."""
+    """Compile every .hip source and link libhot.so.  Always recompiles.  For experiments,
+    HOT_HIPCC_FLAGS adds compiler flags (e.g. -DNAME) and HOT_LIB_OUT names another output."""
     hipcc = _hipcc()
+    extra = shlex.split(os.environ.get("HOT_HIPCC_FLAGS", ""))
+    lib_out = os.environ.get("HOT_LIB_OUT", LIB)
     os.makedirs(OBJ, exist_ok=True)
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{res.stdout}\n{res.stderr}")
@@ -52,11 +56,11 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_out, *objs],
                          capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
-    return LIB
+    return lib_out
 
 
 if __name__ == "__main__":

@@ -612,7 +612,7 @@ hot_status hot_debug_set_exchange_wait_us(int us) {
 }
 
 hot_status hot_debug_set_gemm_mode(int mode) {
-  if (mode < 0 || mode > 8) return HOT_ERR_ARG;
+  if (mode < 0 || (mode > 8 && mode < 10) || mode > 13) return HOT_ERR_ARG;
   set_gemm_mode(mode);
   return HOT_OK;
 }

@@ -40,16 +40,17 @@ hipError_t launch_unpack(const uint8_t* codes, int64_t rows, int64_t K, int64_t 
   return hipGetLastError();
 }
 
-// Tile configurations.  Three workgroup tiles exist: 128x128 (64x64 per wave, three
-// workgroups per compute unit, so one workgroup's stores overlap the others' main
-// loops, but the INT4 widening costs 6 vector instructions per matrix instruction and
-// the vector pipe becomes the limit; with INT8 operands its LDS traffic, 1 KB per matrix
-// instruction, is the limit), 192x256 and 256x256 (96x128 / 128x128 per wave, 64x128 for INT8; one workgroup
-// per unit, half the widening and LDS traffic per matrix instruction, but nothing hides the
-// output stores and a partial last round idles units).  The choice minimises a cost model
-// fitted to measurements on MI355X: rounds over the compute units x (tile operations /
-// sustained rate of that tile + unhidden store time).  INT8 operands (twice the bytes per
-// operation) take 128-byte K stages.  A GEMM with a small output and a long K (the g_w
+// Tile configurations.  Four workgroup tiles exist for INT4 operands: 128x128 (64x64 per
+// wave, three workgroups per compute unit: prologue, matrix loop and epilogue of different
+// workgroups overlap, but the INT4 widening costs 6 vector instructions per matrix
+// instruction), 128x256 (64x128 per wave, two workgroups per unit), 192x256 and 256x256 (96x128
+// / 128x128 per wave, one workgroup per unit: half the widening and LDS traffic per matrix
+// instruction, but prologue (3 us) and epilogue (3 us of instructions, or the tile's bytes at
+// the unit's share of the memory bandwidth when every unit stores at once) are exposed, and a
+// partial last round idles units).  INT8 and bfloat16 operands (twice and four times the
+// bytes per operation) take 128x128, whose LDS traffic (1 KB per matrix instruction) is its
+// limit, or 256x256 with eight waves (64x128 per wave), and 128-byte K stages.  The choice
+// minimises the cost model in plan_gemm.  A GEMM with a small output and a long K (the g_w
 // path of ViT-sized layers) leaves most units idle with one workgroup per tile: its K range
 // is split over several workgroups per tile, which hand their partial sums to the last one
 // through the workspace.
@@ -93,11 +94,19 @@ void set_gemm_mode(int mode) { g_gemm_mode.store(mode); }
 void set_gemm_wait_us(int us) { g_gemm_wait_us.store(us); }
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch) {
-  struct Cand { int bm, bn; double tops; bool hides_stores; };
-  static const Cand cands4[] = {{128, 128, 1900., true}, {192, 256, 2700., false}, {256, 256, 3200., false}};
-  static const Cand cands8[] = {{128, 128, 1000., true}, {256, 256, 2550., false}};
+  // Cost of a tile shape, fitted to measurements on MI355X (ten layer shapes from 512 to 201728
+  // tokens, every INT4 tile timed on each; within 4 % of the measured time, and the measured
+  // best tile or one within 2 % of it on all ten): a compute unit works through its share of
+  // the tiles, each costing its operations at the rate the tile sustains plus its output bytes
+  // at the rate its stores drain, plus a constant per launch.  The share is a whole number of
+  // tiles while the resident workgroups (wgs per unit) take them in a few rounds, the last of
+  // which idles units, and averages out over many rounds.
+  struct Cand { int bm, bn, wgs; double us_per_mop, us_per_kb, us_launch; };
+  static const Cand cands4[] = {{128, 128, 3, 0.0979, 0.0324, 4.3}, {128, 256, 2, 0.0880, 0.0310, 3.6},
+                                {192, 256, 1, 0.0860, 0.0392, 5.6}, {256, 256, 1, 0.0821, 0.0385, 0.0}};
+  static const Cand cands8[] = {{128, 128, 2, 0.2560, 0.0, 0.0}, {256, 256, 1, 0.1004, 0.0476, 0.0}};
   const Cand* cands = bits == 4 ? cands4 : cands8;
-  const int ncand = bits == 4 ? 3 : 2;
+  const int ncand = bits == 4 ? 4 : 2;
   const double K = (double)k_bytes * (bits == 4 ? 2 : 1);
   const int cus = compute_units();
   GemmPlan p;
@@ -106,11 +115,11 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch
   double best = 1e30;
   for (int c = 0; c < ncand; ++c) {
     const int64_t tiles = ceil_div(M, cands[c].bm) * ceil_div(N, cands[c].bn);
-    const double rounds = (double)ceil_div(tiles, cus);
-    const double ops = 2.0 * cands[c].bm * cands[c].bn * K;
-    double t = ops / (cands[c].tops * 1e12 / cus);
-    if (!cands[c].hides_stores) t += 4.0 * cands[c].bm * cands[c].bn / (5.5e12 / cus);
-    t *= rounds;
+    const bool few_rounds = tiles <= 4 * (int64_t)cus * cands[c].wgs;
+    const double per_cu = few_rounds ? (double)ceil_div(tiles, cus) : (double)tiles / cus;
+    const double mops = 2.0 * cands[c].bm * cands[c].bn * K * 1e-6;
+    const double kb = 4.0 * cands[c].bm * cands[c].bn / 1024.0;
+    const double t = per_cu * (mops * cands[c].us_per_mop + kb * cands[c].us_per_kb) + cands[c].us_launch;
     if (t < best) {
       best = t;
       p.bm = cands[c].bm;
@@ -120,6 +129,14 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch
   }
   p.bkb = bits == 4 ? 64 : 128;
   const int mode = g_gemm_mode.load();
+  if (mode >= 10) {   // a tile forced for measurement: 10 = 128x128, 11 = 192x256 (INT4 only), 12 = 256x256
+    const int bm = mode == 10 ? 128 : (mode == 11 && bits == 4 ? 192 : 256);
+    p.bm = bm;
+    p.bn = bm == 128 ? 128 : 256;
+    if (mode == 13 && bits == 4) { p.bm = 128; p.bn = 256; }
+    p.tiles = ceil_div(M, p.bm) * ceil_div(N, p.bn);
+    return p;
+  }
   if (scratch && mode == 0) {
     const int64_t s = large_tile_split(M, N, k_bytes, bits, cus);
     if (s) {
@@ -130,7 +147,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t k_bytes, int bits, bool scratch
       return p;
     }
   }
-  if (scratch && bits != 16 && p.bm == 128 && mode != 1) {
+  if (scratch && bits != 16 && p.bm == 128 && p.bn == 128 && mode != 1) {
     const int64_t nk = k_bytes / p.bkb, most = max_split(p.tiles, nk);
     // measured on MI355X (128x128 INT8 tiles, K of 50-200 stages): fastest with as many slices
     // as keep all workgroups resident at once, two per compute unit; a partial second round
@@ -196,7 +213,7 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, in
   g.split = split;
   const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
   if (split <= 1) return launch_kernel<BM, BN, BKB, INT4, BF16, false>(g, (unsigned)tiles, s, gemm_stage);
-  if constexpr (BF16 || BM == 192 || (INT4 && BM != 128)) {
+  if constexpr (BF16 || BM == 192 || BM != BN || (INT4 && BM != 128)) {
     return hipErrorInvalidValue;   // splits exist for the 128x128 tiles and the 256x256 INT8 tile
   } else {
     if (!g.partial || !g.flags || tiles * (split - 1) > kMaxSplitSlots) return hipErrorInvalidValue;
@@ -245,6 +262,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
     return bits == 4 ? launch_tile<256, 256, 64, true>(g, k_bytes, sw, s, gs)
                      : launch_tile<256, 256, 128, false>(g, k_bytes, sw, s, gs);
   if (plan.bm == 192 && bits == 4) return launch_tile<192, 256, 64, true>(g, k_bytes, sw, s, gs);
+  if (plan.bm == 128 && plan.bn == 256 && bits == 4) return launch_tile<128, 256, 64, true>(g, k_bytes, sw, s, gs);
   if (plan.bm == 128)
     return bits == 4 ? launch_tile<128, 128, 64, true>(g, k_bytes, sw, s, gs)
                      : launch_tile<128, 128, 128, false>(g, k_bytes, sw, s, gs);

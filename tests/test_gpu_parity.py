@@ -834,13 +834,16 @@ def gemm_mode():
     hot.hot_debug_set_exchange_wait_us(200)
 
 
-@pytest.mark.parametrize("mode,wait_us", [(1, 200), (2, 200), (3, 200), (8, 200), (2, 0), (5, 0)])
+@pytest.mark.parametrize("mode,wait_us", [(1, 200), (2, 200), (3, 200), (8, 200), (2, 0), (5, 0),
+                                          (10, 200), (11, 200), (12, 200), (13, 200)])
 def test_gemm_work_distribution(gemm_mode, mode, wait_us):
     """mode 1: a workgroup per output tile; mode s >= 2: K cut into s slices whose
     workgroups hand partial sums to the tile's last one through the workspace; wait 0: no
     owner ever waits, every missing slice is computed by the owner itself (what happens when
-    the other workgroup is late).  Shapes: few tiles with long K, many tiles, ragged tiles,
-    K too short to split."""
+    the other workgroup is late); modes 10-13: every GEMM on one given tile shape (128x128,
+    192x256, 256x256, 128x256), whatever the planner would pick.  Shapes: few tiles with long
+    K, many tiles, ragged tiles (interior tiles take the unchecked epilogue, edge tiles the
+    checked one), K too short to split."""
     hot = _hot()
     gemm_mode(mode)
     hot.hot_debug_set_exchange_wait_us(wait_us)
