@@ -203,6 +203,18 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
                                 hot_quantizer* choice, double* mse_token, double* mse_tensor,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Low-pass rows by the LP_L1 criterion (Supp. B, "Hyper-parameter of HLA": the paper keeps
+ * the top 8 of 16 vectors by the LP_L1 criterion of the 2-D transform it builds on).  Host
+ * only.  Reading taken (the criterion is defined in that earlier work, not in the paper):
+ * the n tokens of a block are a grid in raster order (4 x 4 for n = 16, 8 x 8 for n = 64,
+ * 4 rows of 8 for n = 32); H_n = H_rows (x) H_cols, so natural row k = a * cols + b has
+ * vertical sequency seq(a) and horizontal sequency seq(b); rows are listed by increasing
+ * seq(a) + seq(b), ties by increasing max of the two, then by increasing seq(a).
+ * keep_idx: host, `keep` entries (out), to be passed as hot_config.keep_idx.
+ */
+hot_status hot_lowpass_l1_rows(int32_t block, int32_t keep, int32_t* keep_idx);
+
 /* ---- parity views (not on the timed path): logical forms of packed data ---- */
 
 /* Compressed activation as row-major codes [L*r/n x I] and its scale [1].  With

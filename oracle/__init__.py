@@ -92,6 +92,13 @@ def lowpass_index(n: int, r: int) -> np.ndarray:
     return idx
 
 
+def lowpass_l1_index(n: int, r: int) -> np.ndarray:
+    """The r low-pass rows by the 2-D (LP_L1) criterion of Supp. B, as read in hot_oracle.c."""
+    idx = np.zeros(r, dtype=np.int32)
+    lib().hot_oracle_lowpass_l1_index(C.c_int(n), C.c_int(r), _p(idx))
+    return idx
+
+
 def transform_rows(g, n: int) -> np.ndarray:
     g = _f32(g)
     T = np.empty_like(g)

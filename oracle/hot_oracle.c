@@ -27,8 +27,9 @@
  *     threshold the fractional part is compared against.
  *   - HLA keeps, per block of n tokens, the r rows of H of lowest sequency
  *     (number of sign changes), listed by increasing sequency, unless an
- *     explicit index list is given (Sec. 3.3; the LP_L1 list of Supp. B is
- *     defined in another paper and can be passed in).
+ *     explicit index list is given (Sec. 3.3).  The LP_L1 list of Supp. B is
+ *     defined in another paper; hot_oracle_lowpass_l1_index states the reading
+ *     taken of it (2-D sequency of the block read as a token grid).
  *   - the per-token / per-tensor choice (Sec. 5.2.2) applies to the INT4
  *     quantiser of the rotated g_y on the g_x path, where a token-wise scale
  *     factors out of the product row (Sec. 4.3); operands of the g_w path
@@ -39,9 +40,9 @@
  * Parity status: the fast transform, the quantiser bounds, the integer GEMMs,
  * full-rank HLA, and the end-points of the selection rule are pinned by the
  * CPU tests against closed forms / brute force.  The exact form of the
- * pseudo-stochastic threshold, the default low-pass row choice, and the
- * meaning of "difference of 50 %" are fixed by no value in the paper:
- * "parity unpinned" for those three readings.
+ * pseudo-stochastic threshold, the default low-pass row choice, the LP_L1 row
+ * order, and the meaning of "difference of 50 %" are fixed by no value in the
+ * paper: "parity unpinned" for those four readings.
  */
 #include <math.h>
 #include <stdint.h>
@@ -110,6 +111,52 @@ void hot_oracle_lowpass_index(int n, int r, int32_t* idx /* [r] */) {
   for (int want = 0, got = 0; got < r && want < n; ++want)
     for (int k = 0; k < n; ++k)
       if (hot_oracle_sequency(n, k) == want) { idx[got++] = k; break; }
+}
+
+/* Supp. B ("Hyper-parameter of HLA"): the low-pass rows by the LP_L1 criterion of the 2-D
+ * transform the paper takes from earlier work.  Reading taken here (the criterion itself is
+ * defined in that other paper; parity unpinned): the n tokens of a block are a gh x gw grid
+ * in raster order (token t at row t / gw, column t % gw; gw = gh = sqrt(n) for n = 16, 64;
+ * gh = 4, gw = 8 for n = 32), row k of H_u is read as a gh x gw image, sv(k) and sh(k) are
+ * its sign changes going down a column and along a row, and rows are listed by increasing
+ * sv + sh (the L1 norm of the 2-D sequency), ties by increasing max(sv, sh), then by
+ * increasing sv.  Everything is counted on the explicit matrix. */
+void hot_oracle_lowpass_l1_index(int n, int r, int32_t* idx /* [r] */) {
+  const int gw = n == 32 ? 8 : (n == 16 ? 4 : 8), gh = n / gw;
+  int8_t* H = (int8_t*)malloc((size_t)n * n);
+  int* key = (int*)malloc(sizeof(int) * (size_t)n);
+  hot_oracle_hadamard(n, H);
+  for (int k = 0; k < n; ++k) {
+    const int8_t* img = H + (size_t)k * n;
+    int sv = 0, sh = 0;
+    for (int y = 1; y < gh; ++y) sv += (img[y * gw] != img[(y - 1) * gw]);          /* down column 0 */
+    for (int x = 1; x < gw; ++x) sh += (img[x] != img[x - 1]);                      /* along row 0 */
+    /* H_u(k, .) is a product of a function of y and a function of x, so every column and
+     * every row of the image changes sign at the same places: checked, not assumed */
+    for (int x = 0; x < gw; ++x) {
+      int c = 0;
+      for (int y = 1; y < gh; ++y) c += (img[y * gw + x] != img[(y - 1) * gw + x]);
+      if (c != sv) abort();
+    }
+    for (int y = 0; y < gh; ++y) {
+      int c = 0;
+      for (int x = 1; x < gw; ++x) c += (img[y * gw + x] != img[y * gw + x - 1]);
+      if (c != sh) abort();
+    }
+    const int mx = sv > sh ? sv : sh;
+    key[k] = ((sv + sh) * 64 + mx) * 64 + sv;
+  }
+  for (int got = 0; got < r; ++got) {       /* selection sort: r smallest keys, in order */
+    int bestk = -1;
+    for (int k = 0; k < n; ++k) {
+      int taken = 0;
+      for (int j = 0; j < got; ++j) taken |= (idx[j] == k);
+      if (!taken && (bestk < 0 || key[k] < key[bestk])) bestk = k;
+    }
+    idx[got] = bestk;
+  }
+  free(key);
+  free(H);
 }
 
 /* Sec. 5.1: HT of a [rows x cols] matrix along its columns index (the

@@ -29,7 +29,7 @@ EXPORTS = (
     "hot_default_config", "hot_status_string", "hot_act_buffer_bytes", "hot_workspace_bytes",
     "hot_weight_buffer_bytes", "hot_gx_cached_workspace_bytes", "hot_quantize_weight", "hot_linear_backward_gx_cached",
     "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
-    "hot_linear_backward", "hot_linear_backward_gx_noalloc", "hot_select_quantizer", "hot_debug_unpack_activation",
+    "hot_linear_backward", "hot_linear_backward_gx_noalloc", "hot_lowpass_l1_rows", "hot_select_quantizer", "hot_debug_unpack_activation",
     "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us",
     "hot_debug_set_backward_strategy", "hot_debug_set_gemm_mode", "hot_debug_profile_begin", "hot_debug_profile_end",
     "hot_debug_stage_name", "hot_debug_probe",
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         l.hot_linear_backward.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, C.c_int, vp, vp, vp, sz, vp]
         l.hot_select_quantizer.argtypes = [cfgp, vp, i64, i64, C.POINTER(C.c_int),
                                            C.POINTER(C.c_double), C.POINTER(C.c_double), vp, sz, vp]
+        l.hot_lowpass_l1_rows.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         l.hot_debug_unpack_activation.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
         l.hot_debug_gx_operands.argtypes = [cfgp, vp, i64, i64, i64, C.c_int, vp, vp, vp, vp, vp, vp]
         l.hot_debug_gw_operands.argtypes = [cfgp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
@@ -299,6 +300,13 @@ def hot_select_quantizer(cfg: Config, g_y: torch.Tensor, ws: torch.Tensor,
                                     C.byref(mt), C.byref(mn), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "hot_select_quantizer")
     return choice.value, mt.value, mn.value
+
+
+def hot_lowpass_l1_rows(block: int, keep: int):
+    """The `keep` low-pass rows of a block by the LP_L1 criterion, as a list for Config.keep_idx."""
+    out = (C.c_int32 * keep)()
+    _check(lib().hot_lowpass_l1_rows(int(block), int(keep), out), "hot_lowpass_l1_rows")
+    return [int(k) for k in out]
 
 
 def hot_debug_unpack_activation(cfg: Config, act_buf: torch.Tensor, L: int, I: int, stream=None):

@@ -584,6 +584,30 @@ hot_status hot_select_quantizer(const hot_config* cfg, const float* g_y, int64_t
   return HOT_OK;
 }
 
+hot_status hot_lowpass_l1_rows(int32_t block, int32_t keep, int32_t* keep_idx) {
+  const int n = block, r = keep;
+  if (n != 16 && n != 32 && n != 64) return HOT_ERR_ARG;
+  if (r < 1 || r > n || !keep_idx) return HOT_ERR_ARG;
+  // H_n = H_gh (x) H_gw: natural row k = a * gw + b is the product of row a of H_gh, running
+  // down the token grid, and row b of H_gw, running along it; its 2-D sequency is the pair of
+  // their 1-D sequencies.
+  const int gw = n == 16 ? 4 : 8, gh = n / gw;
+  int key[64];
+  for (int k = 0; k < n; ++k) {
+    const int sv = row_sign_changes(gh, k / gw), sh = row_sign_changes(gw, k % gw);
+    key[k] = ((sv + sh) * 64 + (sv > sh ? sv : sh)) * 64 + sv;
+  }
+  bool taken[64] = {false};
+  for (int j = 0; j < r; ++j) {
+    int best = -1;
+    for (int k = 0; k < n; ++k)
+      if (!taken[k] && (best < 0 || key[k] < key[best])) best = k;
+    taken[best] = true;
+    keep_idx[j] = best;
+  }
+  return HOT_OK;
+}
+
 hot_status hot_debug_unpack_activation(const hot_config* cfg, const void* act_buf, int64_t L,
                                        int64_t I, int8_t* codes, float* scale, void* stream) {
   Config c;

@@ -13,17 +13,20 @@ namespace {
 // computes the missing ones itself; < 0 disables the single-pass kernels.
 std::atomic<int> g_exchange_wait_us{200};
 
-// Launch tags: any sequence that does not repeat within the lifetime of stale slot
-// contents; seeded from the clock so that leftovers of an earlier process differ too.
-uint32_t next_tag() {
-  static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() | 1u};
-  return tag.fetch_add(1, std::memory_order_relaxed);
+// Launch tags: 64 bits that never repeat within a process (a counter) and differ between
+// processes (it starts at the clock's nanosecond count), so that a slot or flag left in a
+// workspace by any earlier launch, of this process or another, is never taken for a fresh one:
+// a leftover would have to match all 64 bits.
+uint64_t next_tag() {
+  static std::atomic<uint64_t> tag{(uint64_t)std::chrono::steady_clock::now().time_since_epoch().count() | 1u};
+  uint64_t t = tag.fetch_add(1, std::memory_order_relaxed);
+  return t ? t : tag.fetch_add(1, std::memory_order_relaxed);   // zero is never a tag
 }
 }  // namespace
 
 void set_exchange_wait_us(int us) { g_exchange_wait_us.store(us); }
 int exchange_wait_us() { return g_exchange_wait_us.load(); }
-uint32_t next_exchange_tag() { return next_tag(); }
+uint64_t next_exchange_tag() { return next_tag(); }
 
 ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_default, bool identity) {
   ColPlan p;
@@ -124,7 +127,7 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, int round, bool*
       per_cu = nb;
       lds_seen = lds;
     }
-    if (tiles > (int64_t)per_cu * cus || tiles > kMaxPartials / 2) return hipSuccess;
+    if (tiles > (int64_t)per_cu * cus || tiles > kMaxExchange) return hipSuccess;
     if (direct_only && tiles * 4 < 5 * (int64_t)cus) return hipSuccess;
     // ... and at most two: with three or more per compute unit both the read and the final
     // stores measured slower (155 MB of 16-row blocks: 48.7 us on 678 workgroups of 7 blocks

@@ -413,9 +413,11 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
 // in registers, publishes the tile's kept abs-max, collects everybody else's, and
 // quantises from registers: one read of the input, one launch.
 //
-// Exchange: slots[b] = (tag << 32 | float bits) written with one 64-bit device-scope
-// atomic store; a slot counts once it carries this launch's tag, so the memory needs no
-// initialisation and no fences.  Waiting is bounded: after `wait_ticks` of the 100 MHz
+// Exchange: workgroup b owns two 64-bit words, (upper half of the launch tag << 32 | float
+// bits) and (lower half << 32 | the same float bits), each written with one device-scope
+// atomic store.  A reader takes the value once both words carry this launch's halves and
+// the same value, so the memory needs no initialisation, the two words need no ordering
+// between them, and a leftover of any earlier launch would have to match all 64 tag bits.  Waiting is bounded: after `wait_ticks` of the 100 MHz
 // wall clock a workgroup computes the maxima still missing itself (each is a pure
 // function of that tile's input), so every wave finishes whether or not the other
 // workgroups are resident, and the result does not depend on who computed what.
@@ -491,7 +493,7 @@ struct OnepassArgs {
   KeepMap map;
   int r, rounding;
   unsigned long long* slots;
-  uint32_t tag;
+  uint64_t tag;
   long long wait_ticks;
   uint8_t* codes;
   int64_t pitch;
@@ -508,7 +510,7 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
   const KeepMap& map = a.map;
   const int r = a.r, rounding = a.rounding;
   unsigned long long* __restrict__ slots = a.slots;
-  const uint32_t tag = a.tag;
+  const uint32_t tag_hi = (uint32_t)(a.tag >> 32), tag_lo = (uint32_t)a.tag;
   const long long wait_ticks = a.wait_ticks;
   uint8_t* __restrict__ codes = a.codes;
   const int64_t pitch = a.pitch;
@@ -518,7 +520,7 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
   constexpr int QMAX = (1 << (BITS - 1)) - 1;
   extern __shared__ __align__(16) uint8_t tile[];
   __shared__ int s_nmiss;
-  __shared__ uint32_t s_miss[64];   // bit b of word b/32: slot b timed out (grid <= 2048)
+  __shared__ uint32_t s_miss[64];   // bit b of word b/32: workgroup b's maximum did not arrive in time
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int bpb = KIND == kKeepGeneric ? r : (KIND == kKeepLowHalf ? N / 2 : (KIND == kKeepAll8 ? N : N / 2));
   const int TB = 4 * KB * bpb, TBP = TB + 4;
@@ -574,8 +576,9 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
     __builtin_amdgcn_sched_barrier(0);
   }
   m = workgroup_max(m);
-  if (tid == 0)
-    __hip_atomic_store(&slots[bid], ((unsigned long long)tag << 32) | __float_as_uint(m),
+  if (tid < 2)
+    __hip_atomic_store(&slots[2 * bid + tid],
+                       ((unsigned long long)(tid == 0 ? tag_hi : tag_lo) << 32) | __float_as_uint(m),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid < 64) s_miss[tid] = 0u;
   if (tid == 0) s_nmiss = 0;
@@ -589,8 +592,10 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
     bool got = false;
     for (int polls = 0; polls < (1 << 16); ++polls) {   // second bound, should the clock stall
       const unsigned long long sv =
-          __hip_atomic_load(&slots[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if ((uint32_t)(sv >> 32) == tag) {
+          __hip_atomic_load(&slots[2 * b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long sw =
+          __hip_atomic_load(&slots[2 * b + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((uint32_t)(sv >> 32) == tag_hi && (uint32_t)(sw >> 32) == tag_lo && (uint32_t)sv == (uint32_t)sw) {
         amax = fmaxf(amax, __uint_as_float((uint32_t)sv));
         got = true;
         break;

@@ -53,7 +53,7 @@ hipError_t try_front(const FrontArgs& f, hipStream_t s, int stage, bool* done) {
       per_cu = nb;
     }
   }
-  if (tiles > (int64_t)per_cu * cus || tiles > kMaxPartials / 2) return hipSuccess;
+  if (tiles > (int64_t)per_cu * cus || tiles > kMaxExchange) return hipSuccess;
   stage_begin(stage, s);
   kern<<<dim3((unsigned)(tiles + f.nrb)), dim3(256), lds, s>>>(f.wa, (int)tiles, f.ra);
   stage_end(stage, s);

@@ -121,6 +121,9 @@ void stage_end(int stage, hipStream_t s);
 
 // Abs-max passes leave up to kMaxPartials per-workgroup maxima; consumers reduce them.
 constexpr int kMaxPartials = 2048;
+// The single-pass kernels exchange maxima through the same array: two 64-bit words per
+// workgroup (each carries half of the launch tag and the value).
+constexpr int kMaxExchange = kMaxPartials / 4;
 
 // Row-direction block WHT + quantise of t [rows x cols] (cols % n == 0).
 //   mode 0: per-token: codes + scales[rows].
@@ -166,7 +169,7 @@ hipError_t launch_col_bf16(const float* x, const RowTiling& rows, int64_t C, con
 // the launch tags of its abs-max exchange (never repeated while stale slots may survive).
 void set_exchange_wait_us(int us);
 int exchange_wait_us();
-uint32_t next_exchange_tag();
+uint64_t next_exchange_tag();
 
 // Both operands of the g_x GEMM from one launch, where that exists (INT4, per-token g_y
 // scales, weights small enough for the single-pass column kernel, O between 257 and 4096):

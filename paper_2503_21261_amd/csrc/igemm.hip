@@ -174,10 +174,6 @@ size_t gemm_scratch_bytes(int64_t M, int64_t N, int64_t k_bytes, int bits) {
 
 namespace {
 
-uint32_t next_gemm_tag() {
-  static std::atomic<uint32_t> tag{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() | 1u};
-  return tag.fetch_add(1, std::memory_order_relaxed);
-}
 
 // Waves per workgroup: 2x2, except 4x2 for the 256x256 INT8 and bfloat16 tiles.  Four waves,
 // alone on their SIMDs, cannot hide the LDS traffic of those operands (two and four times the
@@ -217,7 +213,7 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, in
     return hipErrorInvalidValue;   // splits exist for the 128x128 tiles and the 256x256 INT8 tile
   } else {
     if (!g.partial || !g.flags || tiles * (split - 1) > kMaxSplitSlots) return hipErrorInvalidValue;
-    g.tag = next_gemm_tag();
+    g.tag = next_exchange_tag();   // the process-wide launch tag sequence
     // an image normally arrives before its owner has finished its own slice; the bound only
     // has to cover workgroups that start late: never less than the whole GEMM takes at 200 TOP/s
     int64_t wait_us = g_gemm_wait_us.load();

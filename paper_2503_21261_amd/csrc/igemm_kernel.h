@@ -49,8 +49,8 @@ struct GemmArgs {
   // Split-K launches only (slot = tile * (split - 1) + slice, for all slices but the last):
   int split;                   // K slices
   int32_t* partial;            // [slot][register image of the 256-thread tile]
-  unsigned long long* flags;   // [slot] (tag << 32 | slot + 1) once the image is complete
-  unsigned tag;                // differs from launch to launch: slots never need clearing
+  unsigned long long* flags;   // [slot] = tag once the image is complete
+  unsigned long long tag;      // 64 bits, never zero, never repeated: slots never need clearing
   long long wait_ticks;        // bound on the wait for another workgroup's image (100 MHz ticks)
   const float* row_scale;
   int row_stride;
@@ -430,7 +430,7 @@ void igemm_kernel(const GemmArgs g) {
         --zz;
         const int slot = t * (S - 1) + zz;
         if (tid == 0) {
-          const unsigned long long want = ((unsigned long long)g.tag << 32) | (unsigned)(slot + 1);
+          const unsigned long long want = g.tag;
           const long long start = wall_clock64();
           bool seen;
           do {
@@ -491,8 +491,7 @@ void igemm_kernel(const GemmArgs g) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
       if (tid == 0)
-        __hip_atomic_store(&g.flags[slot], ((unsigned long long)g.tag << 32) | (unsigned)(slot + 1),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&g.flags[slot], g.tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

@@ -156,6 +156,23 @@ def test_workspace_must_be_256_byte_aligned():
     assert lib.hot_compress_activation(c, fake, 64, 64, fake, odd, big, None) == hot.HOT_ERR_ARG
 
 
+def test_lp_l1_rows_match_the_oracles_list():
+    """Host-only helper: the library derives the list from the Kronecker factors of H_n, the
+    oracle counts sign changes on the explicit matrix; every (n, r) must agree."""
+    import ctypes
+    import oracle
+    for n in (16, 32, 64):
+        for r in range(1, n + 1):
+            assert hot.hot_lowpass_l1_rows(n, r) == oracle.lowpass_l1_index(n, r).tolist()
+    buf = (ctypes.c_int32 * 8)()
+    assert hot.lib().hot_lowpass_l1_rows(16, 8, None) == hot.HOT_ERR_ARG
+    assert hot.lib().hot_lowpass_l1_rows(24, 8, buf) == hot.HOT_ERR_ARG
+    assert hot.lib().hot_lowpass_l1_rows(16, 17, buf) == hot.HOT_ERR_ARG
+    # the list is a valid hot_config.keep_idx
+    cfg = hot.Config(block=16, keep=8, keep_idx=hot.hot_lowpass_l1_rows(16, 8))
+    assert hot.hot_act_buffer_bytes(cfg, 512, 768) == 256 + 512 * 768 // 2
+
+
 def test_binding_refuses_host_tensors():
     import torch
     cfg = hot.Config()

@@ -217,6 +217,25 @@ def test_gw_small_shapes(case):
     check_gw(hot, hot.Config(block=n, keep=r, keep_idx=keep), gy, x, "small")
 
 
+@pytest.mark.parametrize("n,r,shape", [(16, 8, (512, 200, 136)), (16, 6, (272, 130, 72)), (64, 16, (1024, 96, 260)),
+                                       (32, 16, (2048, 300, 140)), (16, 8, (50432, 768, 768))])
+def test_gw_with_lp_l1_rows(n, r, shape):
+    """The paper's own choice of kept rows (Supp. B: top r by the LP_L1 criterion) passed as
+    keep_idx: activation compression and the g_w path on the generic kept-row kernels, INT8 and
+    bfloat16, the last shape at config 3's full token count."""
+    L, O, I = shape
+    hot = _hot()
+    keep = hot.hot_lowpass_l1_rows(n, r)
+    assert keep == oracle.lowpass_l1_index(n, r).tolist()
+    x, w, gy = make(L, O, I, seed=91, gy_kind="t4")
+    check_gw(hot, hot.Config(block=n, keep=r, keep_idx=keep), gy, x, "LP_L1 rows")
+    if L <= 4096:
+        check_gw_bf16(hot, hot.Config(block=n, keep=r, keep_idx=keep, gw_bits=16), gy, x, "LP_L1 rows bf16")
+        Oc = O // n * n
+        check_fused(hot, hot.Config(block=n, keep=r, keep_idx=keep), gy[:, :Oc].contiguous(), x, w[:Oc].contiguous(),
+                    True, "LP_L1 rows, one call")
+
+
 def test_gw_nearest_even_and_bf16_inputs():
     hot = _hot()
     x, w, gy = make(512, 96, 80, seed=13, x_kind="bf16")

@@ -166,6 +166,71 @@ def test_full_rank_hla_reproduces_exact_weight_gradient(n):
     assert out["overflow"] == 0
 
 
+def _grid(n):
+    return (4, 4) if n == 16 else ((4, 8) if n == 32 else (8, 8))
+
+
+@pytest.mark.parametrize("n", [16, 32, 64])
+def test_lp_l1_rows_are_the_lowest_two_dimensional_sequencies(n):
+    """The LP_L1 list (Supp. B) as read by the oracle, pinned by what any reading of it must
+    satisfy and by a second construction: rows of H_n as images on the token grid, built here
+    from numpy's Kronecker product of the two 1-D factors rather than from the oracle's matrix."""
+    gh, gw = _grid(n)
+    Hh, Hw = H_ref(gh), H_ref(gw)
+    assert np.array_equal(np.kron(Hh, Hw), H_ref(n))            # the grid reading of a block
+    seq_h = [(np.diff(Hh[a]) != 0).sum() for a in range(gh)]
+    seq_w = [(np.diff(Hw[b]) != 0).sum() for b in range(gw)]
+    l1 = np.array([seq_h[k // gw] + seq_w[k % gw] for k in range(n)])
+    full = oracle.lowpass_l1_index(n, n)
+    assert sorted(full.tolist()) == list(range(n))               # every row once: full rank
+    assert full[0] == 0                                          # the constant vector comes first
+    assert np.all(np.diff(l1[full]) >= 0)                        # non-decreasing L1 norm of the 2-D sequency
+    for r in range(1, n + 1):
+        idx = oracle.lowpass_l1_index(n, r)
+        assert idx.tolist() == full[:r].tolist()                 # prefixes of one order
+        dropped = np.setdiff1d(np.arange(n), idx)
+        assert dropped.size == 0 or l1[idx].max() <= l1[dropped].min()
+    if gh == gw:
+        # turning the grid over (vertical <-> horizontal) maps row a*g + b to b*g + a; whenever the
+        # kept rows end on a boundary of the tie-break's own classes the set does not change
+        key = [(l1[k], max(seq_h[k // gw], seq_w[k % gw])) for k in range(n)]
+        for r in range(1, n + 1):
+            if r == n or key[full[r - 1]] != key[full[r]]:
+                idx = oracle.lowpass_l1_index(n, r)
+                flipped = sorted((k % gw) * gw + k // gw for k in idx)
+                assert flipped == sorted(idx.tolist()), r
+        assert any(key[full[r - 1]] != key[full[r]] for r in (n // 2,))   # the paper's 8 of 16 is such an r
+
+
+def test_lp_l1_sixteen_tokens_keep_eight_is_the_two_by_two_corner_plus_two_edges():
+    """n = 16, r = 8: sequency pairs (vertical, horizontal) with sum <= 2, and of the four with
+    sum 3 the two that are not on an axis: (1,2) and (2,1)."""
+    Hh = H_ref(4)
+    seq = [(np.diff(Hh[a]) != 0).sum() for a in range(4)]
+    pairs = sorted((seq[k // 4], seq[k % 4]) for k in oracle.lowpass_l1_index(16, 8))
+    assert pairs == sorted([(0, 0), (0, 1), (1, 0), (1, 1), (0, 2), (2, 0), (1, 2), (2, 1)])
+
+
+@pytest.mark.parametrize("n", [16, 64])
+def test_lp_l1_full_rank_reproduces_exact_weight_gradient_and_low_rank_is_a_two_d_low_pass(n):
+    L, O, I = 4 * n, 6, 5
+    g = RNG.standard_normal((L, O)).astype(np.float32)
+    x = RNG.standard_normal((L, I)).astype(np.float32)
+    keep = oracle.lowpass_l1_index(n, n)
+    gh_, xh_ = oracle.hla(g, n, n, keep).astype(np.float64), oracle.hla(x, n, n, keep).astype(np.float64)
+    np.testing.assert_allclose(gh_.T @ xh_ / n, g.astype(np.float64).T @ x.astype(np.float64), rtol=0, atol=1e-3)
+    # r = 4: the rows with both sequencies <= 1 span the functions that are constant on the four
+    # quadrants of the grid, so the unquantised result is the sum over quadrants of
+    # (tokens per quadrant) * mean(g_y)^T mean(x): no transform involved
+    gdim = _grid(n)[0]
+    keep4 = oracle.lowpass_l1_index(n, 4)
+    g4, x4 = oracle.hla(g, n, 4, keep4).astype(np.float64), oracle.hla(x, n, 4, keep4).astype(np.float64)
+    def quadrant_means(t):
+        t = t.astype(np.float64).reshape(L // n, 2, gdim // 2, 2, gdim // 2, t.shape[1])
+        return t.mean(axis=(2, 4)).reshape(L // n * 4, -1)
+    np.testing.assert_allclose(g4.T @ x4 / n, (n // 4) * quadrant_means(g).T @ quadrant_means(x), rtol=0, atol=1e-4)
+
+
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("per_token", [False, True])
 def test_quantizer_bounds_range_and_scales(bits, per_token):
