@@ -214,6 +214,21 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, in
   } else {
     if (!g.partial || !g.flags || tiles * (split - 1) > kMaxSplitSlots) return hipErrorInvalidValue;
     g.tag = next_exchange_tag();   // the process-wide launch tag sequence
+    // one rectangle of the tile grid per XCD where the grid divides evenly: the split that
+    // fetches the fewest operand bytes (A row bands once per XCD column, B bands once per XCD row)
+    g.xcd_cols = 0;
+    if (tiles % 8 == 0) {
+      double best = 0.0;
+      for (int rx = 1; rx <= 8; rx *= 2) {
+        const int ry = 8 / rx;
+        if (g.tiles_m % ry != 0 || g.tiles_n % rx != 0) continue;
+        const double fetch = (double)g.M * rx + (double)g.N * ry;
+        if (g.xcd_cols == 0 || fetch < best) {
+          best = fetch;
+          g.xcd_cols = rx;
+        }
+      }
+    }
     // an image normally arrives before its owner has finished its own slice; the bound only
     // has to cover workgroups that start late: never less than the whole GEMM takes at 200 TOP/s
     int64_t wait_us = g_gemm_wait_us.load();
@@ -248,6 +263,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   g.row_stride = row_stride;
   g.col_scale = col_scale;
   g.inv_n = 1.0f / (float)n;
+  g.xcd_cols = 0;
   const int gs = gemm_stage, sw = plan.split;
   if (bits == 16) {
     if (plan.bm == 256) return launch_tile<256, 256, 128, false, true>(g, k_bytes, sw, s, gs);

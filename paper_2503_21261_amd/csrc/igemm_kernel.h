@@ -56,6 +56,7 @@ struct GemmArgs {
   int row_stride;
   const float* col_scale;
   float inv_n;
+  int xcd_cols;          // split-K: the tile grid cut into 8 / xcd_cols x xcd_cols rectangles, one per XCD (0: band walk)
 };
 
 // Workgroup id -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each
@@ -412,9 +413,21 @@ void igemm_kernel(const GemmArgs g) {
     constexpr int IMG = BM * BN;
     const int tiles = g.tiles_m * g.tiles_n, nk = g.nk_total, S = g.split;
     const int z = blockIdx.x / tiles;   // slices in dispatch order: owners (z = S - 1) start last
-    int tm, tn;
-    const int t = xcd_contiguous(blockIdx.x - z * tiles, tiles);
-    tile_of_position(g, t, tm, tn);
+    int tm, tn, t;
+    if (g.xcd_cols > 0) {
+      // Workgroups go to the eight XCDs in turn, each with an L2 of its own.  Every XCD gets one
+      // rectangle of the tile grid, in every slice the same one: an operand row band is then
+      // fetched by the xcd_cols XCDs that share it and by no other (with the band walk below the
+      // bands of a small grid end up on three to eight of them).
+      t = blockIdx.x - z * tiles;          // tiles is a multiple of 8 here: XCD = t % 8
+      const int x = t & 7, j = t >> 3;
+      const int rm = g.tiles_m / (8 / g.xcd_cols), rn = g.tiles_n / g.xcd_cols;
+      tm = (x / g.xcd_cols) * rm + j % rm;
+      tn = (x % g.xcd_cols) * rn + j / rm;
+    } else {
+      t = xcd_contiguous(blockIdx.x - z * tiles, tiles);
+      tile_of_position(g, t, tm, tn);
+    }
     auto slice_begin = [&](int zz) { return (int)(((int64_t)zz * nk) / S); };
     const bool owned = z == S - 1;
     set_tile(tm, tn);

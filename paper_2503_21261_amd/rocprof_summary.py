@@ -3,10 +3,12 @@
     python -m paper_2503_21261_amd.rocprof_summary trace  <..._kernel_trace.csv>
     python -m paper_2503_21261_amd.rocprof_summary counter <..._counter_collection.csv> FETCH_SIZE
 
-`trace`: average / min / max duration per kernel role, a role being the kernel's position
-within one benchmark step (the launch sequence repeats every step).  `counter`: the same
-grouping for one hardware counter, plus the runtime's device-to-device copy kernel when the
-profiled command ran one (bench.py --calibrate-copy), which calibrates the counter's unit.
+Launches are grouped by (kernel, grid size): within one benchmark workload every layer shape
+gives a kernel a grid of its own, so a group is one kernel role of one layer shape.  `trace`:
+calls, average / min / max duration and share of the total per group, in order of first
+launch.  `counter`: the average of one hardware counter per group, plus the runtime's
+device-to-device copy kernel when the profiled command ran one (bench.py --calibrate-copy
+copies 154 927 104 bytes), which calibrates the counter's unit.
 """
 from __future__ import annotations
 
@@ -17,60 +19,53 @@ import sys
 
 
 def _short(name: str):
-    m = re.search(r"hot::(\w+)(<[^>]*>)?", name.replace("(anonymous namespace)::", ""))
+    m = re.search(r"hot::(\w+)(<.*>)?", name.replace("(anonymous namespace)::", ""))
     if m:
-        return m.group(1) + (m.group(2) or "")
-    if "copyBuffer" in name or "direct_copy" in name:
+        args = m.group(2) or ""
+        args = re.sub(r"\(hot::\w+\)", "", args)
+        return m.group(1) + args
+    if "copyBuffer" in name or "direct_copy" in name or "vectorized_elementwise_kernel" in name and "copy" in name.lower():
         return "device_copy"
     return None
 
 
-def _period(names):
-    for p in range(2, 40):
-        if len(names) >= 3 * p and names[:p] == names[p:2 * p] == names[2 * p:3 * p]:
-            return p
-    return None
+def _grid(r) -> str:
+    if "Grid_Size_X" in r:
+        return f"{r.get('Grid_Size_X', '?')}/{r.get('Workgroup_Size_X', '?')}"
+    return f"{r.get('Grid_Size', '?')}/{r.get('Workgroup_Size', '?')}"
 
 
 def trace(path: str) -> str:
     rows = [r for r in csv.DictReader(open(path)) if "hot::" in r["Kernel_Name"]]
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
-    names = [_short(r["Kernel_Name"]) for r in rows]
-    period = _period(names)
     stats = collections.OrderedDict()
-    for i, r in enumerate(rows):
-        key = (i % period if period else 0, names[i])
-        stats.setdefault(key, []).append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
-    out = [f"# launches per step = {period}; {len(rows)} library launches in the trace",
-           f"{'pos':>3} {'kernel':50} {'calls':>5} {'avg_us':>9} {'min_us':>9} {'max_us':>9}  grid/wg"]
-    total = 0.0
-    for (pos, name), ds in sorted(stats.items()):
-        r0 = rows[pos]
-        grid = (f"{r0.get('Grid_Size_X', '?')}x{r0.get('Grid_Size_Y', '?')}x{r0.get('Grid_Size_Z', '?')}"
-                f"/{r0.get('Workgroup_Size_X', '?')}")
-        avg = sum(ds) / len(ds) / 1e3
-        total += avg
-        out.append(f"{pos:>3} {name:50} {len(ds):>5} {avg:9.2f} {min(ds) / 1e3:9.2f} {max(ds) / 1e3:9.2f}  {grid}")
-    out.append(f"sum of averages per step: {total:.1f} us")
+    for r in rows:
+        stats.setdefault((_short(r["Kernel_Name"]), _grid(r)), []).append(
+            int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    total = sum(sum(ds) for ds in stats.values())
+    out = [f"# {len(rows)} library launches in the trace, {total / 1e6:.3f} ms of kernel time",
+           f"{'kernel':72} {'grid/wg':>14} {'calls':>6} {'avg_us':>10} {'min_us':>10} {'max_us':>10} {'share':>6}"]
+    for (name, grid), ds in stats.items():
+        out.append(f"{name[:72]:72} {grid:>14} {len(ds):>6} {sum(ds) / len(ds) / 1e3:10.2f} {min(ds) / 1e3:10.2f} "
+                   f"{max(ds) / 1e3:10.2f} {100.0 * sum(ds) / total:5.1f}%")
     return "\n".join(out)
 
 
 def counter(path: str, which: str) -> str:
     rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == which]
     rows.sort(key=lambda r: int(r["Dispatch_Id"]))
-    seq = [(_short(r["Kernel_Name"]), float(r["Counter_Value"])) for r in rows]
-    seq = [x for x in seq if x[0]]
-    lib = [x for x in seq if x[0] != "device_copy"]
-    period = _period([x[0] for x in lib])
     agg = collections.OrderedDict()
-    for i, (n, v) in enumerate(lib):
-        agg.setdefault((i % period if period else 0, n), []).append(v)
-    out = [f"# {which}: launches per step = {period}"]
-    for (pos, n), vs in sorted(agg.items()):
-        out.append(f"{pos:>3} {n:50} n={len(vs):3d} avg={sum(vs) / len(vs):14.1f}")
-    cp = [v for n, v in seq if n == "device_copy"]
-    if cp:
-        out.append(f"    device_copy (calibration) n={len(cp)} avg={sum(cp) / len(cp):14.1f}")
+    for r in rows:
+        name = _short(r["Kernel_Name"])
+        if name:
+            key = (name, "" if name == "device_copy" else _grid(r))
+            agg.setdefault(key, []).append(float(r["Counter_Value"]))
+    out = [f"# {which}: average per launch",
+           f"{'kernel':72} {'grid/wg':>14} {'calls':>6} {'avg':>16}"]
+    for (name, grid), vs in agg.items():
+        # the runtime also copies small buffers: the calibration copy is the largest
+        avg = max(vs) if name == "device_copy" else sum(vs) / len(vs)
+        out.append(f"{name[:72]:72} {grid:>14} {len(vs):>6} {avg:16.1f}" + (" (largest)" if name == "device_copy" else ""))
     return "\n".join(out)
 
 
