@@ -379,7 +379,10 @@ __global__ __launch_bounds__(256) void col_quant_kernel(
   const int TBP = TB + 4;            // odd number of dwords
   const int64_t nblk = rt.nblk;
   const int64_t tiles_x = (C + CT - 1) / CT;
-  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  // Last tile first: the abs-max pass ended on the rows with the highest index, and what it read
+  // last is what the 256 MB memory-side cache still holds.
+  const int64_t bid = (int64_t)gridDim.x - 1 - blockIdx.x;
+  const int64_t tx = bid % tiles_x, ty = bid / tiles_x;
   const int64_t c0 = tx * CT + lane * VEC;
   const bool col_ok = c0 < C;
 

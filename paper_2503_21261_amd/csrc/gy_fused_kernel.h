@@ -177,7 +177,9 @@ __global__ __launch_bounds__(256) void gy_fused_quant_kernel(
   const int TB = 4 * kbw * bpb, TBP = TB + 4;
   const int64_t nblk = L / N;
   const int64_t tiles_x = (O + kFusedCT - 1) / kFusedCT;
-  const int64_t tx = blockIdx.x % tiles_x, ty = blockIdx.x / tiles_x;
+  // last tile first: the first pass ended there, and the memory-side cache still holds its rows
+  const int64_t bid = (int64_t)gridDim.x - 1 - blockIdx.x;
+  const int64_t tx = bid % tiles_x, ty = bid / tiles_x;
   const int64_t c0 = tx * kFusedCT + lane * 2;
   const bool ok = c0 < O;
   const int64_t row0 = ty * rows_tile;

@@ -61,7 +61,10 @@ __device__ __forceinline__ void row_quant_body(const RowQuantArgs& a, const int6
   float amax_tensor = 0.0f;
   if (mode == 2) amax_tensor = block_max_of(partials, npartials);
 
-  for (int64_t rb = bid; rb < nrb; rb += nbid) {
+  for (int64_t rb0 = bid; rb0 < nrb; rb0 += nbid) {
+    // the second pass of the per-tensor form starts where the first one ended: those rows are
+    // what the memory-side cache still holds
+    const int64_t rb = mode == 2 ? nrb - 1 - rb0 : rb0;
     const int64_t row = rb * RPB + rl;
     const bool row_ok = row < rows;
     const float4* src = reinterpret_cast<const float4*>(t + row * (int64_t)cols);
