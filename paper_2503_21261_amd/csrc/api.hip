@@ -250,7 +250,7 @@ size_t hot_workspace_bytes(const hot_config* cfg, int64_t L, int64_t O, int64_t 
   if (tok_shape_ok(c, L, O) && tok_shape_ok(c, L, I)) {
     const size_t a = gw_layout(c, L, O, I).total;
     need = a > need ? a : need;
-    if (gx_shape_ok(c, L, O, I) && shared_gy_passes_exist(c)) {
+    if (gx_shape_ok(c, L, O, I)) {   // hot_linear_backward keeps both operand sets at once
       const size_t b = fused_layout(c, L, O, I).total;
       need = b > need ? b : need;
     }
@@ -523,12 +523,23 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
   const ActLayout a = act_layout(c, L, I);
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
-  if (!shared_gy_passes(c, L, O)) {
-    st = hot_linear_backward_gx(cfg, g_y, w, L, O, I, gy_quantizer, g_x, ws, ws_bytes, stream);
-    if (st != HOT_OK) return st;
-    return hot_linear_backward_gw(cfg, g_y, act_buf, L, O, I, g_w, ws, ws_bytes, stream);
-  }
   if (ws_bytes < f.total) return HOT_ERR_WORKSPACE;
+  if (!shared_gy_passes(c, L, O)) {
+    // The two separate paths, with both operand transforms ahead of both GEMMs (the workspace
+    // holds the two operand sets side by side): the second reader of g_y follows the first
+    // while part of the tensor is still in the memory-side cache, and no bandwidth-bound
+    // kernel starts right behind a GEMM, at the clock the matrix load has left the chip at.
+    st = gx_operands(c, g_y, w, L, O, I, gy_quantizer, base, f.gx, s);
+    if (st != HOT_OK) return st;
+    st = gw_operand(c, g_y, L, O, base + f.qgh, f.gw.pitch, (float*)(base + f.s_gh), (float*)(base + kHeaderBytes), s);
+    if (st != HOT_OK) return st;
+    st = gx_gemm(c, base + f.gx.qw, (const float*)(base + f.gx.scalars), L, I, gy_quantizer, g_x, base, f.gx,
+                 f.partial, s);
+    if (st != HOT_OK) return st;
+    HOT_TRY(gemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial,
+                 nullptr, g_w, (const float*)(base + f.s_gh), 0, (const float*)act_buf, c.n, s, kStGwGemm));
+    return HOT_OK;
+  }
   float* s_w = (float*)(base + f.gx.scalars);
   float* s_gh = (float*)(base + f.s_gh);
   float* part_a = (float*)(base + kHeaderBytes);
