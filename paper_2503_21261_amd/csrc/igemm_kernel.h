@@ -37,6 +37,12 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
+// One fp32 store with the streaming (non-temporal) cache hint, OFF bytes past p.
+template <int OFF>
+__device__ __forceinline__ void store_streaming(float* p, float v) {
+  asm volatile("global_store_dword %0, %1, off offset:%2 nt" : : "v"(p), "v"(v), "n"(OFF) : "memory");
+}
+
 struct GemmArgs {
   const uint8_t* A;
   const uint8_t* B;
@@ -56,6 +62,7 @@ struct GemmArgs {
   int row_stride;
   const float* col_scale;
   float inv_n;
+  int stream_out;        // fp32 output with non-temporal stores
   int xcd_cols;          // split-K: the tile grid cut into 8 / xcd_cols x xcd_cols rectangles, one per XCD (0: band walk)
 };
 
@@ -347,24 +354,45 @@ void igemm_kernel(const GemmArgs g) {
       // tile where this one takes 3.
       const unsigned lane_byte = 4u * (unsigned)((wm0 + 4 * (lane >> 5)) * g.N + nl0);   // < 2^32: inside one tile
       char* const tile = reinterpret_cast<char*>(g.out_f32 + ((int64_t)m0 * g.N + n0));
+      auto store_tile = [&](auto nt_c) {
+        constexpr bool NT = decltype(nt_c)::value;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          typedef float v4f __attribute__((ext_vector_type(4)));
-          const v4f rs4 = *reinterpret_cast<const v4f*>(&s_rowfac[wm0 + i * 32 + 8 * q + 4 * (lane >> 5)]);
+          for (int q = 0; q < 4; ++q) {
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const v4f rs4 = *reinterpret_cast<const v4f*>(&s_rowfac[wm0 + i * 32 + 8 * q + 4 * (lane >> 5)]);
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            char* const row = tile + (int64_t)(i * 32 + 8 * q + r) * g.N * 4;   // uniform
+            for (int r = 0; r < 4; ++r) {
+              char* const row = tile + (int64_t)(i * 32 + 8 * q + r) * g.N * 4;   // uniform
+              if constexpr (NT) {
+                // written as an instruction: two branches that differ only in a store's cache
+                // hint are merged by the compiler, and the hint is lost
+                float* dst = reinterpret_cast<float*>(row + lane_byte);
+                static_for<TN>([&](auto jc) {
+                  constexpr int j = decltype(jc)::value;
+                  float val;
+                  if constexpr (BF16) val = acc[i][j][4 * q + r] * rs4[r];
+                  else val = (float)acc[i][j][4 * q + r] * rs4[r];
+                  store_streaming<j * 128>(dst, val);
+                });
+              } else {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-              float* const dst = reinterpret_cast<float*>(row + j * 128 + lane_byte);
-              if constexpr (BF16) *dst = acc[i][j][4 * q + r] * rs4[r];
-              else *dst = (float)acc[i][j][4 * q + r] * rs4[r];
+                for (int j = 0; j < TN; ++j) {
+                  float* const dst = reinterpret_cast<float*>(row + j * 128 + lane_byte);
+                  if constexpr (BF16) *dst = acc[i][j][4 * q + r] * rs4[r];
+                  else *dst = (float)acc[i][j][4 * q + r] * rs4[r];
+                }
+              }
             }
           }
         }
-      }
+      };
+      // Streaming stores keep the output out of the way of the operand tiles in L2 (with a
+      // short K the 4 MB of an XCD otherwise lose the weight operand to the output between two
+      // bands of tiles); with a long K per tile they measured slower than plain stores.
+      if (g.stream_out) store_tile(std::true_type{});
+      else store_tile(std::false_type{});
     } else if (g.out_f32) {
       float* obase = g.out_f32 + ((int64_t)m0 * g.N + n0);
 #pragma unroll
