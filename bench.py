@@ -171,6 +171,7 @@ class Job:
         share a shape pooled under the layer's name."""
         hot, cfg = self.hot, self.cfg
         acc = {}
+        self.launch_sequence = []   # "<layer>.<role>" of every launch of one step, in order
 
         def take(lname, prof):
             for role, (ms, cnt) in prof.items():
@@ -178,15 +179,20 @@ class Job:
                 a[0] += ms
                 a[1] += cnt
 
-        for _ in range(steps):
+        for step in range(steps):
             for k, (name, l) in enumerate(self.layers):
                 hot.hot_debug_profile_begin()
                 self.compress(k)
                 take(name.split(".")[-1], hot.hot_debug_profile_end())
+                if step == 0:
+                    self.launch_sequence += [f"{name.split('.')[-1]}.{r}" for r in hot.hot_debug_profile_sequence()]
             for k in range(len(self.layers) - 1, -1, -1):
                 hot.hot_debug_profile_begin()
                 self.backward(k)
                 take(self.layers[k][0].split(".")[-1], hot.hot_debug_profile_end())
+                if step == 0:
+                    lname = self.layers[k][0].split(".")[-1]
+                    self.launch_sequence += [f"{lname}.{r}" for r in hot.hot_debug_profile_sequence()]
         shapes = {name.split(".")[-1]: (l, self.quant[k]) for k, (name, l) in enumerate(self.layers)}
         table = {}
         for (lname, role), (ms, cnt) in acc.items():
@@ -248,7 +254,7 @@ def summarise(job, ms_per_step, table, layers, finite, torch):
                act_buffer_bytes=job.act_bytes, act_fp32_bytes=job.fp32_bytes,
                act_ratio=round(job.act_bytes / job.fp32_bytes, 4),
                peak_device_bytes=int(torch.cuda.max_memory_allocated()),
-               outputs_finite=finite, layers=layers, kernels=table)
+               outputs_finite=finite, layers=layers, kernels=table, launch_sequence=job.launch_sequence)
     if job.selected:
         out["select_quantizer"] = job.selected
     return out
@@ -525,6 +531,7 @@ def main() -> int:
         "peak_device_bytes_streamed": streamed_peak,
         "outputs_finite": head["outputs_finite"],
         "roofline": roof, "cpu_baseline": cpu, "layers": head["layers"], "kernels": head["kernels"],
+        "launch_sequence": head["launch_sequence"],
     }
     if "select_quantizer" in head:
         out["select_quantizer"] = head["select_quantizer"]

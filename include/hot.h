@@ -296,6 +296,11 @@ hot_status hot_debug_profile_begin(void);
  * HOT_NUM_STAGES entries). */
 hot_status hot_debug_profile_end(float* stage_ms, int64_t* stage_launches);
 
+/* The stages of the recording that the last hot_debug_profile_end closed, in launch order:
+ * writes up to `capacity` stage ids to `stages` (host; may be NULL) and returns how many
+ * launches there were. */
+int64_t hot_debug_profile_sequence(int32_t* stages, int64_t capacity);
+
 const char* hot_debug_stage_name(int stage);
 
 /* Machine-peak probes (context for the roofline figures, not the method): one launch of

@@ -31,7 +31,7 @@ EXPORTS = (
     "hot_debug_unpack_weight", "hot_compress_activation", "hot_linear_backward_gx", "hot_linear_backward_gw",
     "hot_linear_backward", "hot_linear_backward_gx_noalloc", "hot_lowpass_l1_rows", "hot_select_quantizer", "hot_debug_unpack_activation",
     "hot_debug_gx_operands", "hot_debug_gw_operands", "hot_debug_fused_operands", "hot_debug_set_exchange_wait_us",
-    "hot_debug_set_backward_strategy", "hot_debug_set_gemm_mode", "hot_debug_profile_begin", "hot_debug_profile_end",
+    "hot_debug_set_backward_strategy", "hot_debug_set_gemm_mode", "hot_debug_profile_begin", "hot_debug_profile_end", "hot_debug_profile_sequence",
     "hot_debug_stage_name", "hot_debug_probe",
 )
 HOT_NUM_STAGES = 15
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         l.hot_debug_profile_begin.argtypes = []
         l.hot_debug_profile_end.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int64)]
         l.hot_debug_probe.argtypes = [C.c_int, vp, sz, C.c_int, vp]
+        l.hot_debug_profile_sequence.argtypes = [C.POINTER(C.c_int32), C.c_int64]
         l.hot_weight_buffer_bytes.argtypes = [cfgp, i64, i64]
         l.hot_weight_buffer_bytes.restype = sz
         l.hot_gx_cached_workspace_bytes.argtypes = [cfgp, i64, i64, i64]
@@ -98,8 +99,9 @@ def lib() -> C.CDLL:
         l.hot_linear_backward_gx_cached.argtypes = [cfgp, vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
         l.hot_debug_unpack_weight.argtypes = [cfgp, vp, i64, i64, vp, vp, vp]
         for name in EXPORTS[6:]:
-            if name != "hot_debug_stage_name":
+            if name not in ("hot_debug_stage_name", "hot_debug_profile_sequence"):
                 getattr(l, name).restype = C.c_int
+        l.hot_debug_profile_sequence.restype = C.c_int64
         l.hot_debug_stage_name.argtypes = [C.c_int]
         l.hot_debug_stage_name.restype = C.c_char_p
         _lib = l
@@ -401,6 +403,14 @@ def hot_debug_profile_end():
     _check(lib().hot_debug_profile_end(ms, cnt), "hot_debug_profile_end")
     return {lib().hot_debug_stage_name(i).decode(): (float(ms[i]), int(cnt[i]))
             for i in range(HOT_NUM_STAGES) if cnt[i]}
+
+
+def hot_debug_profile_sequence():
+    """Stage names of the recording closed by the last hot_debug_profile_end, in launch order."""
+    n = int(lib().hot_debug_profile_sequence(None, 0))
+    buf = (C.c_int32 * max(n, 1))()
+    lib().hot_debug_profile_sequence(buf, n)
+    return [lib().hot_debug_stage_name(int(buf[i])).decode() for i in range(n)]
 
 
 def hot_debug_probe(kind: int, buf: torch.Tensor, iters: int = 1, stream=None) -> None:

@@ -17,6 +17,7 @@ std::mutex g_mu;
 bool g_on = false;
 std::vector<Record> g_records;
 std::vector<hipEvent_t> g_pool;
+std::vector<int> g_sequence;   // stages of the last finished recording, in launch order
 
 hipEvent_t take_event() {
   if (!g_pool.empty()) {
@@ -74,7 +75,9 @@ hot_status hot_debug_profile_end(float* stage_ms, int64_t* stage_launches) {
     stage_launches[i] = 0;
   }
   hot_status st = HOT_OK;
+  hot::g_sequence.clear();
   for (auto& r : hot::g_records) {
+    hot::g_sequence.push_back(r.stage);
     float ms = 0.0f;
     if (hipEventSynchronize(r.stop) != hipSuccess ||
         hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
@@ -88,6 +91,13 @@ hot_status hot_debug_profile_end(float* stage_ms, int64_t* stage_launches) {
   }
   hot::g_records.clear();
   return st;
+}
+
+int64_t hot_debug_profile_sequence(int32_t* stages, int64_t capacity) {
+  std::lock_guard<std::mutex> lock(hot::g_mu);
+  const int64_t n = (int64_t)hot::g_sequence.size();
+  for (int64_t i = 0; stages && i < n && i < capacity; ++i) stages[i] = hot::g_sequence[(size_t)i];
+  return n;
 }
 
 const char* hot_debug_stage_name(int stage) {
