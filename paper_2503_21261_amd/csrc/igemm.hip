@@ -217,7 +217,12 @@ hipError_t launch_tile(GemmArgs g, int64_t k_bytes, int split, hipStream_t s, in
     // one rectangle of the tile grid per XCD where the grid divides evenly: the split that
     // fetches the fewest operand bytes (A row bands once per XCD column, B bands once per XCD row)
     g.xcd_cols = 0;
-    if (tiles % 8 == 0) {
+    if (BM == 128 && 8 % split == 0 && g.tiles_m % (8 / split) == 0) {
+      // a slice per group of XCDs: the fewest operand bytes of all (ViT-B proj g_w, 36 tiles in
+      // 8 slices: 50.5 -> 45 us; the 256x256 split measured slower this way, 385 against 360 us
+      // on the ViT-L g_w GEMM, and keeps the rectangles)
+      g.xcd_cols = -1;
+    } else if (tiles % 8 == 0) {
       double best = 0.0;
       for (int rx = 1; rx <= 8; rx *= 2) {
         const int ry = 8 / rx;

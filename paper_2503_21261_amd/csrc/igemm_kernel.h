@@ -63,7 +63,8 @@ struct GemmArgs {
   const float* col_scale;
   float inv_n;
   int stream_out;        // fp32 output with non-temporal stores
-  int xcd_cols;          // split-K: the tile grid cut into 8 / xcd_cols x xcd_cols rectangles, one per XCD (0: band walk)
+  int xcd_cols;          // split-K: > 0: the tile grid cut into 8 / xcd_cols x xcd_cols rectangles, one per XCD;
+                         // < 0: XCDs dealt to the K slices; 0: band walk
 };
 
 // Workgroup id -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each
@@ -440,9 +441,18 @@ void igemm_kernel(const GemmArgs g) {
   } else {
     constexpr int IMG = BM * BN;
     const int tiles = g.tiles_m * g.tiles_n, nk = g.nk_total, S = g.split;
-    const int z = blockIdx.x / tiles;   // slices in dispatch order: owners (z = S - 1) start last
+    int z = blockIdx.x / tiles;   // slices in dispatch order: owners (z = S - 1) start last
     int tm, tn, t;
-    if (g.xcd_cols > 0) {
+    if (g.xcd_cols < 0) {
+      // S divides 8: the XCDs are dealt to the slices, 8 / S to each, and the XCDs of a slice
+      // share its tiles by row bands.  An A row band of a slice is then fetched by one XCD, a B
+      // band by 8 / S of them: the whole GEMM fetches A once and B 8 / S times.
+      const int per = 8 / S, x = blockIdx.x & 7, j = blockIdx.x >> 3;   // XCD, index within it
+      z = x / per;
+      t = (x % per) * (tiles / per) + j;
+      tm = t / g.tiles_n;
+      tn = t % g.tiles_n;
+    } else if (g.xcd_cols > 0) {
       // Workgroups go to the eight XCDs in turn, each with an L2 of its own.  Every XCD gets one
       // rectangle of the tile grid, in every slice the same one: an operand row band is then
       // fetched by the xcd_cols XCDs that share it and by no other (with the band walk below the
