@@ -36,24 +36,90 @@ __device__ __forceinline__ void load_block_raw(const float* __restrict__ rows, i
 }
 
 // Row-direction butterflies h = 1 .. N/2 for the two adjacent elements (a, b) a lane
-// holds; a block of N columns spans N/2 neighbouring lanes.
+// holds, two rows at a time; a block of N columns spans N/2 neighbouring lanes.
+//
+// Across lanes a butterfly is ONE instruction, own = partner * c + own with the partner read
+// through a DPP permute and c = +1 in the lane that holds the lower element, -1 in the upper
+// one.  The product by +-1 is exact, so the single rounding is that of the plain sum or
+// difference.  The upper lane thereby computes b - a where the transform has a - b: a lane
+// carries its values with the sign (-1)^(number of stages in which it was the upper lane),
+// which a lane and its partner share at every stage (they differ only in the bit of that
+// stage), so c stays +-1.  Magnitudes are unaffected; `flip` is the sign bit to xor into the
+// reciprocal scale where the values are quantised: (sigma t) * (sigma inv) = t * inv exactly.
+//
+// The compiler folds a DPP permute into an add or a multiply but not into a multiply-add,
+// hence the assembly.  It does not see DPP instructions inside it, so the hazards are waited
+// for here: a vector write of EXEC needs 5 wait states before a DPP instruction (s_nop 4 at
+// the top covers that and the 2 wait states after a vector write of a source register);
+// within the block four independent chains put three instructions between a write and its
+// DPP read; s_nop 1 at the end covers a DPP read the compiler may place right behind it.
 template <int N>
-__device__ __forceinline__ void fwht_row2(float& a, float& b, int lane) {
-  const float x = a + b, y = a - b;  // h = 1
-  a = x;
-  b = y;
-#define HOT_STAGE2(MASK)                     \
-  {                                          \
-    const bool up = (lane & MASK) != 0;      \
-    a = butterfly_lanes<MASK>(a, up);        \
-    b = butterfly_lanes<MASK>(b, up);        \
-  }
-  HOT_STAGE2(1)                         // h = 2
-  HOT_STAGE2(2)                         // h = 4
-  HOT_STAGE2(4)                         // h = 8
-  if constexpr (N >= 32) HOT_STAGE2(8)  // h = 16
-#undef HOT_STAGE2
+struct LaneSigns {
+  float c1, c2, c4, c8;
+  uint32_t flip;
+};
+template <int N>
+__device__ __forceinline__ LaneSigns<N> lane_signs(int lane) {
+  static_assert(N == 16 || N == 32, "block size of the fused kernels");
+  LaneSigns<N> s;
+  s.c1 = (lane & 1) ? -1.0f : 1.0f;
+  s.c2 = (lane & 2) ? -1.0f : 1.0f;
+  s.c4 = (lane & 4) ? -1.0f : 1.0f;
+  s.c8 = (lane & 8) ? -1.0f : 1.0f;
+  s.flip = (__builtin_popcount((unsigned)lane & (N == 32 ? 15u : 7u)) & 1) ? 0x80000000u : 0u;
+  return s;
 }
+
+#define HOT_DPP_ALL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+#define HOT_FMAC4(CTRL, C)                                    \
+  "v_fmac_f32_dpp %0, %0, " C " " CTRL HOT_DPP_ALL            \
+  "v_fmac_f32_dpp %1, %1, " C " " CTRL HOT_DPP_ALL            \
+  "v_fmac_f32_dpp %2, %2, " C " " CTRL HOT_DPP_ALL            \
+  "v_fmac_f32_dpp %3, %3, " C " " CTRL HOT_DPP_ALL
+// id ^ 4 and id ^ 8 are two mirrors each: the first as a move into a temporary, the second
+// folded into the multiply-add
+#define HOT_FMAC4_VIA(CTRL1, CTRL2, C)                        \
+  "v_mov_b32_dpp %4, %0 " CTRL1 HOT_DPP_ALL                   \
+  "v_mov_b32_dpp %5, %1 " CTRL1 HOT_DPP_ALL                   \
+  "v_mov_b32_dpp %6, %2 " CTRL1 HOT_DPP_ALL                   \
+  "v_mov_b32_dpp %7, %3 " CTRL1 HOT_DPP_ALL                   \
+  "v_fmac_f32_dpp %0, %4, " C " " CTRL2 HOT_DPP_ALL           \
+  "v_fmac_f32_dpp %1, %5, " C " " CTRL2 HOT_DPP_ALL           \
+  "v_fmac_f32_dpp %2, %6, " C " " CTRL2 HOT_DPP_ALL           \
+  "v_fmac_f32_dpp %3, %7, " C " " CTRL2 HOT_DPP_ALL
+
+template <int N>
+__device__ __forceinline__ void fwht_row2_pair(float& a0, float& b0, float& a1, float& b1,
+                                               const LaneSigns<N>& s) {
+  const float x0 = a0 + b0, y0 = a0 - b0;  // h = 1
+  const float x1 = a1 + b1, y1 = a1 - b1;
+  a0 = x0;
+  b0 = y0;
+  a1 = x1;
+  b1 = y1;
+  float t0, t1, t2, t3;
+  if constexpr (N == 16) {
+    asm volatile("s_nop 4\n\t"
+                 HOT_FMAC4("quad_perm:[1,0,3,2]", "%8")                           // h = 2
+                 HOT_FMAC4("quad_perm:[2,3,0,1]", "%9")                           // h = 4
+                 HOT_FMAC4_VIA("quad_perm:[3,2,1,0]", "row_half_mirror", "%10")   // h = 8
+                 "s_nop 1"
+                 : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+                 : "v"(s.c1), "v"(s.c2), "v"(s.c4));
+  } else {
+    asm volatile("s_nop 4\n\t"
+                 HOT_FMAC4("quad_perm:[1,0,3,2]", "%8")                           // h = 2
+                 HOT_FMAC4("quad_perm:[2,3,0,1]", "%9")                           // h = 4
+                 HOT_FMAC4_VIA("quad_perm:[3,2,1,0]", "row_half_mirror", "%10")   // h = 8
+                 HOT_FMAC4_VIA("row_half_mirror", "row_mirror", "%11")            // h = 16
+                 "s_nop 1"
+                 : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+                 : "v"(s.c1), "v"(s.c2), "v"(s.c4), "v"(s.c8));
+  }
+}
+#undef HOT_FMAC4_VIA
+#undef HOT_FMAC4
+#undef HOT_DPP_ALL
 
 // One halving step of the transposing maximum: the lane keeps one half of its CNT*2
 // rows and receives its partner's maxima for that half.
@@ -98,6 +164,7 @@ __global__ __launch_bounds__(256) void gy_fused_absmax_kernel(
   const int64_t nblk = L / N;
   const int64_t tiles_x = (O + kFusedCT - 1) / kFusedCT;
   const int64_t tiles_y = (nblk + 4 * kbw - 1) / (4 * kbw);
+  const LaneSigns<N> signs = lane_signs<N>(lane);
   float mh = 0.0f, mr = 0.0f;
   for (int64_t t = blockIdx.x; t < tiles_x * tiles_y; t += gridDim.x) {
     const int64_t tx = t % tiles_x, ty = t / tiles_x;
@@ -129,9 +196,10 @@ __global__ __launch_bounds__(256) void gy_fused_absmax_kernel(
       }
       float m[N];
 #pragma unroll
-      for (int k = 0; k < N; ++k) {
-        fwht_row2<N>(v[0][k], v[1][k], lane);
+      for (int k = 0; k < N; k += 2) {
+        fwht_row2_pair<N>(v[0][k], v[1][k], v[0][k + 1], v[1][k + 1], signs);
         m[k] = fmaxf(fabsf(v[0][k]), fabsf(v[1][k]));
+        m[k + 1] = fmaxf(fabsf(v[0][k + 1]), fabsf(v[1][k + 1]));
       }
       if constexpr (PER_TOKEN) {
         const float rm = rows_max_across_lanes<N>(m, lane);
@@ -183,6 +251,7 @@ __global__ __launch_bounds__(256) void gy_fused_quant_kernel(
   const int64_t c0 = tx * kFusedCT + lane * 2;
   const bool ok = c0 < O;
   const int64_t row0 = ty * rows_tile;
+  const LaneSigns<N> signs = lane_signs<N>(lane);
 
   const float amax_h = block_max_of(part_hla, npartials);
   const float inv_h = quant_inv(amax_h, 127);
@@ -250,11 +319,12 @@ __global__ __launch_bounds__(256) void gy_fused_quant_kernel(
 #pragma unroll
       for (int k4 = 0; k4 < N / 4; ++k4) {
         uint32_t word = 0;
+        fwht_row2_pair<N>(v[0][4 * k4], v[1][4 * k4], v[0][4 * k4 + 1], v[1][4 * k4 + 1], signs);
+        fwht_row2_pair<N>(v[0][4 * k4 + 2], v[1][4 * k4 + 2], v[0][4 * k4 + 3], v[1][4 * k4 + 3], signs);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int k = 4 * k4 + e;
-          fwht_row2<N>(v[0][k], v[1][k], lane);
-          const float inv = PER_TOKEN ? s_inv[slot * N + k] : inv_t;
+          const float inv = __uint_as_float(__float_as_uint(PER_TOKEN ? s_inv[slot * N + k] : inv_t) ^ signs.flip);
           const int a = quant_code(v[0][k], inv, QMAXG, rounding);
           const int b = quant_code(v[1][k], inv, QMAXG, rounding);
           word |= (uint32_t)((a & 0xF) | ((b & 0xF) << 4)) << (8 * e);
@@ -273,11 +343,11 @@ __global__ __launch_bounds__(256) void gy_fused_quant_kernel(
 #pragma unroll
       for (int k2 = 0; k2 < N / 2; ++k2) {
         uint32_t word = 0;
+        fwht_row2_pair<N>(v[0][2 * k2], v[1][2 * k2], v[0][2 * k2 + 1], v[1][2 * k2 + 1], signs);
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int k = 2 * k2 + e;
-          fwht_row2<N>(v[0][k], v[1][k], lane);
-          const float inv = PER_TOKEN ? s_inv[slot * N + k] : inv_t;
+          const float inv = __uint_as_float(__float_as_uint(PER_TOKEN ? s_inv[slot * N + k] : inv_t) ^ signs.flip);
           const int a = quant_code(v[0][k], inv, QMAXG, rounding);
           const int b = quant_code(v[1][k], inv, QMAXG, rounding);
           word |= (uint32_t)((a & 0xFF) | ((b & 0xFF) << 8)) << (16 * e);
