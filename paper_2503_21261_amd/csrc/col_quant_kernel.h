@@ -675,13 +675,13 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
   if (bid == 0 && tid == 0) *scale = quant_scale(amax, QMAX);
 
   // A lane's codes of consecutive blocks are consecutive bytes of its column's output row:
-  // with enough of them (and a compile-time kept list) they are stored straight from
-  // registers, 16 or 8 bytes at a time; otherwise they go through the LDS tile.
+  // with enough of them (and a compile-time kept list) they are packed in registers and leave
+  // as 16-byte pieces after a wave-private transposition (or 8 bytes at a time straight from
+  // registers where a run is not a multiple of 16); otherwise they go through the LDS tile.
   constexpr bool kDirect = onepass_direct_store<N, KIND, KB>();
   if constexpr (kDirect) {
     constexpr int BPB = static_bpb<N, KIND>();
-    // all blocks are packed first and stored afterwards, so that the pieces of one output
-    // line reach L2 back to back and leave it as one full line
+    // all blocks are packed first and stored afterwards
     auto emit = [&](auto rounding_c) {
       constexpr int ROUNDING = decltype(rounding_c)::value;
       uint32_t d[KB][VEC][BPB / 4];
@@ -691,7 +691,52 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
         for (int vi = 0; vi < VEC; ++vi) pack_kept_codes<N, KIND, ROUNDING>(v[kb][vi], inv, d[kb][vi]);
       }
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (BPB == 8 && KB % 2 == 0) {
+      constexpr int RUN = KB * BPB;   // consecutive output bytes of a lane's column
+      if constexpr (RUN % 16 == 0 && RUN >= 64) {
+        // Transposed through a wave-private part of the LDS tile so that a store instruction
+        // writes whole runs: the wave's codes are staged as [column][16-byte chunk] (each lane
+        // its own runs), read back in linear order, and lane l of store `it` then holds chunk
+        // (it * 64 + l) % CH of column (it * 64 + l) / CH: neighbouring lanes write
+        // neighbouring 16 bytes of one output row (RUN bytes per row and instruction) instead
+        // of 64 lanes writing 16 bytes each into 64 different rows, which left L2 as partial
+        // lines (HLA of the ViT-B g_y: 35.8 -> 19.2 MB written for 19.4 MB of codes, 42 -> 38.5 us).
+        // Only this wave touches the staging area and a wave's LDS instructions are performed
+        // in order, so no workgroup barrier is needed.  Runs below 64 bytes keep the plain
+        // stores: the extra LDS round trip costs such a short kernel more than it saves
+        // (ViT-B activation, 48-byte runs: 19.0 against 17.5 us).
+        constexpr int CH = RUN / 16;
+        uint8_t* wt = tile + (size_t)w * (CT * RUN);
+#pragma unroll
+        for (int vi = 0; vi < VEC; ++vi) {
+#pragma unroll
+          for (int ch = 0; ch < CH; ++ch) {
+            uint4 val;
+            if constexpr (BPB == 8) {   // two consecutive blocks per chunk
+              val = make_uint4(d[2 * ch][vi][0], d[2 * ch][vi][1], d[2 * ch + 1][vi][0], d[2 * ch + 1][vi][1]);
+            } else {
+              constexpr int PER = BPB / 16;   // chunks per block
+              const int kb = ch / PER, dw = 4 * (ch % PER);
+              val = make_uint4(d[kb][vi][dw], d[kb][vi][dw + 1], d[kb][vi][dw + 2], d[kb][vi][dw + 3]);
+            }
+            *reinterpret_cast<uint4*>(wt + (lane * VEC + vi) * RUN + ch * 16) = val;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint8_t* out = codes + gb0 * BPB;
+#pragma unroll
+        for (int it = 0; it < VEC * CH; ++it) {
+          const int f = it * 64 + lane;
+          const int colw = f / CH, ch = f - colw * CH;
+          const uint4 val = *reinterpret_cast<const uint4*>(wt + f * 16);
+          const int64_t c = tx * CT + colw;
+          // a chunk whose first block exists is stored whole: a partner block past the end
+          // holds zero codes, which is what the padding up to the pitch holds anyway
+          if (c < C && gb0 + (ch * 16) / BPB < nblk)
+            *reinterpret_cast<uint4*>(out + c * pitch + ch * 16) = val;
+        }
+      } else if constexpr (BPB == 8 && KB % 2 == 0) {
         // 8-byte blocks: two consecutive blocks make one aligned 16-byte store (a wave's
         // first block is even; a partner block past the end holds zero codes, which is what
         // the padding up to the pitch holds anyway)
