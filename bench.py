@@ -370,6 +370,28 @@ def probe_peaks(torch, hot):
     ops = 2.0 * 32 * 32 * 32 * 16 * iters * 256 * 4
     out["mfma_i8_TOPS_constant_operands"] = round(ops / timed(2, buf, iters, 3) / 1e12, 1)
     out["mfma_i8_TOPS_random_operands"] = round(ops / timed(3, buf, iters, 6) / 1e12, 1)
+
+    # What a streaming read costs right behind another kernel: behind a 1 GB write (whose tail
+    # is still on its way from the memory-side cache to HBM), a 50 MB write, a 1 GB read and a
+    # register-only matrix loop of about 0.5 ms.  Median of 8, the read alone timed.
+    a = torch.zeros(1000 * 1000 * 1000 // 4, dtype=torch.float32, device="cuda")
+    b = torch.zeros(1000 * 1000 * 1000 // 4, dtype=torch.float32, device="cuda")
+    nbytes = a.numel() * 4 - 4096
+    before = {"idle": None, "read_1GB": (0, b, 1), "write_1GB": (1, b, 1),
+              "write_50MB": (1, b[:50 * 1000 * 1000 // 4], 1), "matrix_loop": (3, buf, 1500)}
+    for name, pre in before.items():
+        ts = []
+        for _ in range(8):
+            torch.cuda.synchronize()
+            time.sleep(0.01)
+            if pre is not None:
+                hot.hot_debug_probe(*pre)
+            ev0.record()
+            hot.hot_debug_probe(0, a, 1)
+            ev1.record()
+            torch.cuda.synchronize()
+            ts.append(ev0.elapsed_time(ev1) * 1e-3)
+        out[f"hbm_read_GBps_1GB_behind_{name}"] = round(nbytes / sorted(ts)[len(ts) // 2] / 1e9, 1)
     return out
 
 
