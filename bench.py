@@ -364,6 +364,7 @@ def probe_peaks(torch, hot):
         nbytes = buf.numel() * 4 - 4096
         out[f"hbm_read_GBps_{mb}MB"] = round(nbytes / timed(0, buf, 1, 10) / 1e9, 1)
         out[f"hbm_write_GBps_{mb}MB"] = round(nbytes / timed(1, buf, 1, 10) / 1e9, 1)
+        out[f"hbm_write_streaming_hint_GBps_{mb}MB"] = round(nbytes / timed(4, buf, 1, 10) / 1e9, 1)
         del buf
     buf = torch.zeros(1 << 20, dtype=torch.int32, device="cuda")
     iters = 4000

@@ -304,7 +304,8 @@ int64_t hot_debug_profile_sequence(int32_t* stages, int64_t capacity);
 const char* hot_debug_stage_name(int stage);
 
 /* Machine-peak probes (context for the roofline figures, not the method): one launch of
- * kind 0 = read `bytes` of buf, 1 = write them, 2 / 3 = `iters` x 16 int8 32x32x32 matrix
+ * kind 0 = read `bytes` of buf, 1 = write them (4 = with the streaming, non-temporal, hint the
+ * GEMM epilogue uses), 2 / 3 = `iters` x 16 int8 32x32x32 matrix
  * instructions per wave on all SIMDs with constant / pseudo-random register operands
  * (buf, >= 1 MiB, receives a checksum).  The caller times the launch. */
 hot_status hot_debug_probe(int kind, void* buf, size_t bytes, int iters, void* stream);

@@ -22,6 +22,14 @@ __global__ __launch_bounds__(256) void probe_write_kernel(float4* __restrict__ p
     p[i] = make_float4(v, v, v, v);
 }
 
+// The same with the streaming (non-temporal) hint the GEMM epilogue uses.
+typedef float pv4f __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void probe_write_nt_kernel(pv4f* __restrict__ p, size_t n, float v) {
+  const pv4f q = {v, v, v, v};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+    __builtin_nontemporal_store(q, &p[i]);
+}
+
 // 16 independent 32x32 accumulators per wave, operands in registers.
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_operands,
                                                          int* __restrict__ sink) {
@@ -58,6 +66,7 @@ extern "C" hot_status hot_debug_probe(int kind, void* buf, size_t bytes, int ite
     case 1: probe_write_kernel<<<dim3(4096), dim3(256), 0, s>>>((float4*)buf, n4, 1.0f); break;
     case 2:
     case 3: probe_mfma_kernel<<<dim3(256), dim3(256), 0, s>>>(iters, kind == 3, (int*)buf); break;
+    case 4: probe_write_nt_kernel<<<dim3(4096), dim3(256), 0, s>>>((pv4f*)buf, n4, 1.0f); break;
     default: return HOT_ERR_ARG;
   }
   return hipGetLastError() == hipSuccess ? HOT_OK : HOT_ERR_DEVICE;
