@@ -805,6 +805,22 @@ def test_single_pass_16_row_blocks_with_an_odd_block_count():
     check_gw(hot, hot.Config(block=16, keep=8), gy, x, "odd block count")
 
 
+def test_single_pass_transposed_stores_with_ragged_edges():
+    """Runs of 64 code bytes or more per lane leave the single-pass kernel through a
+    wave-private transposition (a store instruction then writes whole runs of an output row).
+    Shapes that take that path (4 blocks per wave of 32 rows, 8 of 16 rows) with a last column
+    tile that is partly empty and a last row tile that holds a single block: every code, the
+    padding (through the GEMM, which reads it as K) and the scale must be the oracle's."""
+    hot = _hot()
+    for (n, L, O, I, seed) in [(32, 32 * 385, 200, 1000, 51), (16, 16 * 1443, 48, 1000, 52)]:
+        x, w, gy = make(L, O, I, seed=seed)
+        check_gw(hot, hot.Config(block=n, keep=n // 2), gy, x, f"transposed stores n={n}")
+    # the weight operand of the g_x path (INT4, all rows kept): 2592 x 4040, few tokens
+    x, w, gy = make(64, 2592, 4040, seed=53)
+    check_gx(hot, hot.Config(block=32, keep=16), gy, w, True, "transposed stores, weights")
+    check_gx(hot, hot.Config(block=32, keep=16), gy, w, False, "transposed stores, weights, per tensor")
+
+
 def test_config2_two_pass_column_kernels(exchange_wait):
     """configs[1] with the single-pass kernels switched off (x and w then take the same
     two-pass kernels as tensors too large for the register files)."""
