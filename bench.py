@@ -165,6 +165,39 @@ class Job:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def timed_graph(self, steps, warmup):
+        """The same step recorded once into a HIP graph (hot_config.replayable: launch tags from
+        an epoch in the workspace, one more one-thread launch per call) and replayed: what a
+        launch-bound step costs without the host's launch overhead.  ms per replay."""
+        torch = self.torch
+        eager_cfg = self.cfg
+        self.cfg = self.hot.Config(block=eager_cfg.block, keep=eager_cfg.keep, gw_bits=eager_cfg.gw_bits,
+                                   sample_tokens=eager_cfg.sample_tokens, replayable=True)
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                self.stream = side
+                self.step()            # launch plans are made on first use
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                self.stream = torch.cuda.current_stream()
+                self.step()
+            torch.cuda.synchronize()
+            for _ in range(warmup):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps
+        finally:
+            self.cfg = eager_cfg
+            self.stream = torch.cuda.current_stream()
+
     def kernel_table(self, steps):
         """The same steps with HIP events around every kernel (recorded on the launch stream),
         one layer call at a time; kernels are keyed "<layer>.<role>", layers of a chain that
@@ -445,9 +478,13 @@ def run_job(torch, hot, hot_inputs, wl, args, want_cpu):
     torch.cuda.reset_peak_memory_stats()
     job = Job(torch, hot, hot_inputs, wl, args)
     ms = job.timed(args.steps, args.warmup)
+    # a step recorded into a HIP graph and replayed, for the workloads where launches matter
+    ms_graph = job.timed_graph(args.steps, args.warmup) if (len(job.layers) <= 4 and ms < 5.0) else None
     table = job.kernel_table(max(1, min(args.steps, 5 if len(job.layers) > 8 else 20)))
     layers, finite = job.layer_table()
     res = summarise(job, ms, table, layers, finite, torch)
+    if ms_graph is not None:
+        res["graph_replay_us_per_step"] = round(ms_graph * 1e3, 2)
     cpu = None
     if want_cpu:
         cpu = cpu_baseline(job, args.cpu_seconds, args.cpu_sample_tokens or (16384 if len(job.layers) > 1 else 0))
@@ -558,6 +595,8 @@ def main() -> int:
     }
     if "select_quantizer" in head:
         out["select_quantizer"] = head["select_quantizer"]
+    if "graph_replay_us_per_step" in head:
+        out["graph_replay_us_per_step"] = head["graph_replay_us_per_step"]
     if others:
         out["workloads"] = others
     print(json.dumps(out))

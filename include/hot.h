@@ -24,10 +24,16 @@
  *     launch, so a failing call has launched nothing.  Inputs must be finite.
  *   - Two calls that share a workspace or an output must be ordered by the
  *     caller (same stream, or events).
- *   - Calls must not be recorded into a HIP graph: the kernels whose workgroups
- *     exchange values through the workspace (single-pass transforms, split-K
- *     GEMM) tell a launch's values from stale ones by a tag chosen on the host
- *     per call, and a replayed graph would repeat it.
+ *   - HIP graphs: the kernels whose workgroups exchange values through the
+ *     workspace (single-pass transforms, split-K GEMM) tell a launch's values
+ *     from stale ones by a tag.  By default the host chooses it per call, and a
+ *     replayed graph would repeat it: such calls must not be recorded.  With
+ *     hot_config.replayable set, every call first advances a 64-bit epoch in the
+ *     workspace (one more one-thread kernel) and the kernels derive their tags
+ *     from it on the device, so that the call may be recorded and replayed (with
+ *     the buffers it was recorded with; call it once with the same shapes before
+ *     recording: launch plans are made on first use).  hot_select_quantizer waits
+ *     for its result and cannot be recorded either way.
  */
 #ifndef HOT_H
 #define HOT_H
@@ -74,10 +80,13 @@ typedef struct {
                               separately and pads its last block with zero tokens, so
                               S need not be a multiple of n (ViT: S = 197); then
                               L*r/n below reads B * ceil(S/n) * r                       */
+  int32_t replayable;      /* 0: launch tags from the host (default).  1: from an epoch in
+                              the workspace that every call advances with one more
+                              launch; calls may then be recorded into a HIP graph        */
 } hot_config;
 
 /* Fills *cfg with the paper's defaults: n = 16, r = 8, low-sequency rows, INT4 /
- * INT8, pseudo-stochastic rounding, threshold 0.5, one run of tokens. */
+ * INT8, pseudo-stochastic rounding, threshold 0.5, one run of tokens, host tags. */
 void hot_default_config(hot_config* cfg);
 
 const char* hot_status_string(hot_status s);

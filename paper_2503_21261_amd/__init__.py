@@ -41,7 +41,7 @@ HOT_WS_PREFIX_BYTES = 24832
 class hot_config(C.Structure):
     _fields_ = [("block", C.c_int32), ("keep", C.c_int32), ("keep_idx", C.POINTER(C.c_int32)),
                 ("gx_bits", C.c_int32), ("gw_bits", C.c_int32), ("rounding", C.c_int32),
-                ("lqs_threshold", C.c_float), ("sample_tokens", C.c_int32)]
+                ("lqs_threshold", C.c_float), ("sample_tokens", C.c_int32), ("replayable", C.c_int32)]
 
 
 class HotError(RuntimeError):
@@ -123,6 +123,7 @@ class Config:
     rounding: int = HOT_ROUND_PSEUDO_STOCHASTIC
     lqs_threshold: float = 0.5
     sample_tokens: int = 0
+    replayable: bool = False     # launch tags from the workspace epoch: calls may be recorded into a HIP graph
 
     def reduced_tokens(self, L: int) -> int:
         """L' = tokens after HLA: L*r/n, or B * ceil(S/n) * r with per-sample tiling."""
@@ -136,6 +137,7 @@ class Config:
         cfg.gx_bits, cfg.gw_bits = int(self.gx_bits), int(self.gw_bits)
         cfg.rounding, cfg.lqs_threshold = int(self.rounding), float(self.lqs_threshold)
         cfg.sample_tokens = int(self.sample_tokens)
+        cfg.replayable = 1 if self.replayable else 0
         if self.keep_idx is None:
             cfg.keep_idx = None
             self._keep_arr = None

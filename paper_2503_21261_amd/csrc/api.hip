@@ -47,6 +47,9 @@ hot_status resolve_config(const hot_config* cfg, Config* out) {
   out->rounding = cfg->rounding;
   out->lqs_threshold = cfg->lqs_threshold;
   out->sample_tokens = cfg->sample_tokens;
+  if (cfg->replayable != 0 && cfg->replayable != 1) return HOT_ERR_ARG;
+  out->replayable = cfg->replayable == 1;
+  out->epoch = nullptr;
   out->lowpass_default = cfg->keep_idx == nullptr;
   for (int k = 0; k < 64; ++k) out->map.pos[k] = -1;
   for (int j = 0; j < r; ++j) {
@@ -199,6 +202,21 @@ KeepMap identity_map(int n) {
     if (e_ != hipSuccess) return HOT_ERR_DEVICE; \
   } while (0)
 
+// A replayable call keeps a 64-bit epoch among the workspace's scalars and advances it before
+// anything else; the kernels that exchange values through the workspace move their launch tags
+// by it (effective_tag), so that a replay of a recorded call never repeats a tag.  The epoch
+// needs no initial value: it only has to change.
+__global__ void advance_epoch_kernel(unsigned long long* epoch) { *epoch = *epoch + 1ull; }
+
+hipError_t begin_call(Config& c, void* ws, hipStream_t s) {
+  c.epoch = nullptr;
+  if (!c.replayable) return hipSuccess;
+  unsigned long long* e = (unsigned long long*)((uint8_t*)ws + kEpochOffset);
+  advance_epoch_kernel<<<dim3(1), dim3(1), 0, s>>>(e);
+  c.epoch = e;
+  return hipGetLastError();
+}
+
 }  // namespace
 }  // namespace hot
 
@@ -216,6 +234,7 @@ void hot_default_config(hot_config* cfg) {
   cfg->rounding = HOT_ROUND_PSEUDO_STOCHASTIC;
   cfg->lqs_threshold = 0.5f;
   cfg->sample_tokens = 0;
+  cfg->replayable = 0;
 }
 
 const char* hot_status_string(hot_status s) {
@@ -270,6 +289,7 @@ hot_status hot_compress_activation(const hot_config* cfg, const float* x, int64_
   const ActLayout a = act_layout(c, L, I);
   uint8_t* base = (uint8_t*)act_buf;
   float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
+  HOT_TRY(begin_call(c, ws, s));
   if (c.gw_bits == 16) {
     HOT_TRY(launch_col_bf16(x, row_tiling(c, L), I, c, base + a.codes, a.pitch, (float*)base, s, kStActQuant));
     return HOT_OK;
@@ -303,6 +323,7 @@ hot_status hot_quantize_weight(const hot_config* cfg, const float* w, int64_t O,
   const WeightLayout wl = weight_layout(c, O, I);
   uint8_t* base = (uint8_t*)wq_buf;
   float* partials = (float*)((uint8_t*)ws + kHeaderBytes);
+  HOT_TRY(begin_call(c, ws, s));
   HOT_TRY(launch_col_quant(w, RowTiling{O / c.n, 0, 1}, I, c, c.n, identity_map(c.n), true, c.gx_bits, base + wl.codes,
                            wl.pitch, (float*)base, partials, s, kStWAbsmax, kStWQuant));
   return HOT_OK;
@@ -312,14 +333,16 @@ namespace {
 
 // One GEMM on K-contiguous operands of `pitch` bytes, planned for its shape, with the
 // scratch region at base + partial_off and the flag slots of the workspace prefix.
-hipError_t gemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t pitch, int bits,
-                uint8_t* base, size_t partial_off, int32_t* out_i32, float* out_f32,
+hipError_t gemm(const Config& c, const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t pitch,
+                int bits, uint8_t* base, size_t partial_off, int32_t* out_i32, float* out_f32,
                 const float* row_scale, int row_stride, const float* col_scale, int n, hipStream_t s,
                 int stage = -1) {
   return launch_igemm(A, B, M, N, pitch, pitch, bits, plan_gemm(M, N, pitch, bits, true),
                       (int32_t*)(base + partial_off), (unsigned long long*)(base + kGemmFlagsOffset),
-                      out_i32, out_f32, row_scale, row_stride, col_scale, n, s, stage);
+                      out_i32, out_f32, row_scale, row_stride, col_scale, n, s, stage, c.epoch);
 }
+
+
 
 // g_x path, first half: the rotated, quantised g_y operand (codes at g.qg, scales at g.sg).
 hot_status gx_rows(const Config& c, const float* g_y, int64_t L, int64_t O, hot_quantizer gy_quantizer,
@@ -358,7 +381,7 @@ hot_status gx_operands(const Config& c, const float* g_y, const float* w, int64_
 hot_status gx_gemm(const Config& c, const uint8_t* qw, const float* s_w, int64_t L, int64_t I,
                    hot_quantizer gy_quantizer, float* g_x, uint8_t* base, const GxLayout& g,
                    size_t partial_off, hipStream_t s) {
-  HOT_TRY(gemm(base + g.qg, qw, L, I, g.pitch, c.gx_bits, base, partial_off, nullptr, g_x,
+  HOT_TRY(gemm(c, base + g.qg, qw, L, I, g.pitch, c.gx_bits, base, partial_off, nullptr, g_x,
                (const float*)(base + g.sg), gy_quantizer == HOT_Q_PER_TOKEN ? 1 : 0, s_w, c.n, s, kStGxGemm));
   return HOT_OK;
 }
@@ -409,6 +432,7 @@ hot_status hot_linear_backward_gx(const hot_config* cfg, const float* g_y, const
   if (!ws || !aligned256(ws)) return HOT_ERR_ARG;
   const GxLayout g = gx_layout(c, L, O, I);
   if (ws_bytes < g.total) return HOT_ERR_WORKSPACE;
+  HOT_TRY(begin_call(c, ws, (hipStream_t)stream));
   return gx_run(c, g_y, w, L, O, I, gy_quantizer, g_x, (uint8_t*)ws, g, (hipStream_t)stream);
 }
 
@@ -455,6 +479,7 @@ hot_status hot_linear_backward_gx_noalloc(const hot_config* cfg, const float* g_
   if (st != HOT_OK) return st;
   // Nothing in the scratch has to start at zero: exchange slots and split-K flags are told
   // from an earlier call's by a per-launch tag, everything else is written before it is read.
+  HOT_TRY(begin_call(c, base, (hipStream_t)stream));
   return gx_run(c, g_y, w, L, O, I, gy_quantizer, g_x, base, g, (hipStream_t)stream);
 }
 
@@ -474,6 +499,7 @@ hot_status hot_linear_backward_gx_cached(const hot_config* cfg, const float* g_y
   if (ws_bytes < gx_cached_total(g)) return HOT_ERR_WORKSPACE;
   const WeightLayout wl = weight_layout(c, O, I);
   const uint8_t* wb = (const uint8_t*)wq_buf;
+  HOT_TRY(begin_call(c, ws, (hipStream_t)stream));
   st = gx_rows(c, g_y, L, O, gy_quantizer, (uint8_t*)ws, g, (hipStream_t)stream);
   if (st != HOT_OK) return st;
   return gx_gemm(c, wb + wl.codes, (const float*)wb, L, I, gy_quantizer, g_x, (uint8_t*)ws, g,
@@ -500,9 +526,10 @@ hot_status hot_linear_backward_gw(const hot_config* cfg, const float* g_y, const
   uint8_t* qg = base + g.qg;
   const uint8_t* abase = (const uint8_t*)act_buf;
 
+  HOT_TRY(begin_call(c, ws, s));
   st = gw_operand(c, g_y, L, O, qg, g.pitch, s_g, part_g, s);
   if (st != HOT_OK) return st;
-  HOT_TRY(gemm(qg, abase + a.codes, O, I, g.pitch, c.gw_bits, base, g.partial, nullptr, g_w, s_g, 0,
+  HOT_TRY(gemm(c, qg, abase + a.codes, O, I, g.pitch, c.gw_bits, base, g.partial, nullptr, g_w, s_g, 0,
                (const float*)abase, c.n, s, kStGwGemm));
   return HOT_OK;
 }
@@ -524,6 +551,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
   hipStream_t s = (hipStream_t)stream;
   uint8_t* base = (uint8_t*)ws;
   if (ws_bytes < f.total) return HOT_ERR_WORKSPACE;
+  HOT_TRY(begin_call(c, ws, s));
   if (!shared_gy_passes(c, L, O)) {
     // The two separate paths, with both operand transforms ahead of both GEMMs (the workspace
     // holds the two operand sets side by side): the second reader of g_y follows the first
@@ -538,7 +566,7 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
     st = gx_gemm(c, base + f.gx.qw, (const float*)(base + f.gx.scalars), L, I, gy_quantizer, g_x, base, f.gx,
                  f.partial, s);
     if (st != HOT_OK) return st;
-    HOT_TRY(gemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial,
+    HOT_TRY(gemm(c, base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial,
                  nullptr, g_w, (const float*)(base + f.s_gh), 0, (const float*)act_buf, c.n, s, kStGwGemm));
     return HOT_OK;
   }
@@ -557,9 +585,9 @@ hot_status hot_linear_backward(const hot_config* cfg, const float* g_y, const fl
                            part_a, s, kStWAbsmax, kStWQuant));
   HOT_TRY(launch_gy_fused(g_y, L, O, c, per_token, qg, f.gx.pitch, s_g, qgh, f.gw.pitch, s_gh, part_a,
                           part_b, (float*)(base + f.rowpart), s, kStGyFusedAbsmax, kStGyFusedQuant));
-  HOT_TRY(gemm(qg, qw, L, I, f.gx.pitch, c.gx_bits, base, f.partial, nullptr, g_x, s_g,
+  HOT_TRY(gemm(c, qg, qw, L, I, f.gx.pitch, c.gx_bits, base, f.partial, nullptr, g_x, s_g,
                per_token ? 1 : 0, s_w, c.n, s, kStGxGemm));
-  HOT_TRY(gemm(qgh, abase + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial, nullptr, g_w, s_gh,
+  HOT_TRY(gemm(c, qgh, abase + a.codes, O, I, f.gw.pitch, c.gw_bits, base, f.partial, nullptr, g_w, s_gh,
                0, (const float*)abase, c.n, s, kStGwGemm));
   return HOT_OK;
 }
@@ -688,7 +716,7 @@ hot_status hot_debug_gx_operands(const hot_config* cfg, void* ws, int64_t L, int
                            hipMemcpyDeviceToDevice, s));
   if (w_scale) HOT_TRY(hipMemcpyAsync(w_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(gemm(base + g.qg, base + g.qw, L, I, g.pitch, c.gx_bits, base, g.partial, acc, nullptr,
+    HOT_TRY(gemm(c, base + g.qg, base + g.qw, L, I, g.pitch, c.gx_bits, base, g.partial, acc, nullptr,
                  nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
@@ -708,7 +736,7 @@ hot_status hot_debug_gw_operands(const hot_config* cfg, void* ws, const void* ac
   if (gy_codes) HOT_TRY(launch_unpack(base + g.qg, O, g.Lr, g.pitch, c.gw_bits, 1, gy_codes, s));
   if (gy_scale) HOT_TRY(hipMemcpyAsync(gy_scale, base + g.scalars, 4, hipMemcpyDeviceToDevice, s));
   if (acc)
-    HOT_TRY(gemm(base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, c.gw_bits, base,
+    HOT_TRY(gemm(c, base + g.qg, (const uint8_t*)act_buf + a.codes, O, I, g.pitch, c.gw_bits, base,
                  g.partial, acc, nullptr, nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }
@@ -734,7 +762,7 @@ hot_status hot_debug_fused_operands(const hot_config* cfg, void* ws, const void*
   if (gyT_codes) HOT_TRY(launch_unpack(base + f.qgh, O, f.gw.Lr, f.gw.pitch, 8, 1, gyT_codes, s));
   if (gyT_scale) HOT_TRY(hipMemcpyAsync(gyT_scale, base + f.s_gh, 4, hipMemcpyDeviceToDevice, s));
   if (acc_gw)
-    HOT_TRY(gemm(base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, 8, base, f.partial,
+    HOT_TRY(gemm(c, base + f.qgh, (const uint8_t*)act_buf + a.codes, O, I, f.gw.pitch, 8, base, f.partial,
                  acc_gw, nullptr, nullptr, 0, nullptr, c.n, s));
   return HOT_OK;
 }

@@ -72,6 +72,7 @@ struct ColArgs {
   int64_t pitch;
   float* scale;
   float* partials;
+  const unsigned long long* epoch;
 };
 
 template <int N, int VEC, int KIND>
@@ -141,7 +142,7 @@ hipError_t try_onepass(const ColArgs& a, hipStream_t s, int sq, int round, bool*
     if (wait_us > 0 && wait_us < stream_us) wait_us = stream_us;
     stage_begin(sq, s);
     const OnepassArgs oa{a.x, a.rows, a.C, a.map, a.r, a.rounding,
-                         reinterpret_cast<unsigned long long*>(a.partials), next_tag(),
+                         reinterpret_cast<unsigned long long*>(a.partials), next_tag(), a.epoch,
                          (long long)(wait_us * 100), a.codes, a.pitch, a.scale};
     kern<<<dim3((unsigned)tiles), dim3(256), lds, s>>>(oa);
     stage_end(sq, s);
@@ -213,7 +214,7 @@ hipError_t launch_col_quant(const float* x, const RowTiling& rows, int64_t C, co
   if (rows.nblk <= 0 || C <= 0) return hipSuccess;
   if (bits == 4 && !(identity && r == cfg.n)) return hipErrorInvalidValue;
   const ColPlan p = plan_col(rows.nblk, C, cfg.n, r, bits, cfg.lowpass_default && !identity, identity);
-  const ColArgs a{x, rows, C, map, r, cfg.rounding, codes, pitch, scale, partials};
+  const ColArgs a{x, rows, C, map, r, cfg.rounding, codes, pitch, scale, partials, cfg.epoch};
   switch (cfg.n) {
     case 16: return launch_n<16>(a, p, s, stage_absmax, stage_quant);
     case 32: return launch_n<32>(a, p, s, stage_absmax, stage_quant);

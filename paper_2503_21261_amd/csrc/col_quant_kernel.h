@@ -497,6 +497,7 @@ struct OnepassArgs {
   int r, rounding;
   unsigned long long* slots;
   uint64_t tag;
+  const unsigned long long* epoch;   // replayable calls: the tag is moved by *epoch
   long long wait_ticks;
   uint8_t* codes;
   int64_t pitch;
@@ -513,7 +514,8 @@ __device__ __forceinline__ void onepass_body(const OnepassArgs& a, const int bid
   const KeepMap& map = a.map;
   const int r = a.r, rounding = a.rounding;
   unsigned long long* __restrict__ slots = a.slots;
-  const uint32_t tag_hi = (uint32_t)(a.tag >> 32), tag_lo = (uint32_t)a.tag;
+  const unsigned long long tag = effective_tag(a.tag, a.epoch);
+  const uint32_t tag_hi = (uint32_t)(tag >> 32), tag_lo = (uint32_t)tag;
   const long long wait_ticks = a.wait_ticks;
   uint8_t* __restrict__ codes = a.codes;
   const int64_t pitch = a.pitch;

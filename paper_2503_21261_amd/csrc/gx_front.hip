@@ -100,7 +100,7 @@ hipError_t launch_w_and_rows(const float* w, int64_t O, int64_t I, const Config&
   for (int k = 0; k < 64; ++k) id.pos[k] = (int8_t)(k < cfg.n ? k : -1);
   FrontArgs f;
   f.wa = OnepassArgs{w, RowTiling{O / cfg.n, 0, 1}, I, id, cfg.n, cfg.rounding,
-                     reinterpret_cast<unsigned long long*>(slots), next_exchange_tag(),
+                     reinterpret_cast<unsigned long long*>(slots), next_exchange_tag(), cfg.epoch,
                      (long long)(wait_us * 100), qw, pitch, s_w};
   f.ra = RowQuantArgs{g_y, L, (int)O, 4, cfg.rounding, 0, qg, pitch, s_g, nullptr, 0};
   f.nrb = 0;

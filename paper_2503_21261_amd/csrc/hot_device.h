@@ -34,6 +34,16 @@ __device__ __forceinline__ float lane_xor(float v) {
   return __int_as_float(r);
 }
 
+// Launch tag of a kernel whose workgroups exchange values through the workspace: the host's
+// per-launch tag, or, in a replayable call, that tag moved by the workspace epoch which every
+// such call advances first (a replayed graph repeats the host's tag but not the epoch).
+__device__ __forceinline__ unsigned long long effective_tag(unsigned long long host_tag,
+                                                            const unsigned long long* epoch) {
+  if (!epoch) return host_tag;
+  const unsigned long long t = host_tag + *epoch * 0x9E3779B97F4A7C15ull;
+  return t ? t : 1ull;   // zero is never a tag
+}
+
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, lane_xor<1>(v));
   v = fmaxf(v, lane_xor<2>(v));

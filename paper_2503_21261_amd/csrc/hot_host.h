@@ -34,6 +34,8 @@ struct Config {
   int keep[64];   // r natural-order indices, in output order
   KeepMap map;    // inverse of keep
   bool lowpass_default;
+  bool replayable;   // launch tags derived from the workspace epoch (HIP graph replays)
+  const unsigned long long* epoch;   // device address of that epoch for the current call, or null
 };
 
 hot_status resolve_config(const hot_config* cfg, Config* out);
@@ -46,6 +48,8 @@ constexpr int64_t kHeaderBytes = 256;
 // Every workspace starts with 256 bytes of scalars (scales, results), two arrays
 // of per-workgroup partial maxima and the flags of a split-K GEMM's partial sums.
 constexpr int64_t kPartialBytes = 2048 * 4;
+// Offset of the 64-bit epoch among the scalars (used by replayable calls only).
+constexpr int64_t kEpochOffset = 128;
 constexpr int kMaxSplitSlots = 1024;
 constexpr int64_t kGemmFlagsOffset = kHeaderBytes + 2 * kPartialBytes;
 constexpr int64_t kWsPrefix = kGemmFlagsOffset + kMaxSplitSlots * 8;
@@ -185,12 +189,13 @@ hipError_t launch_w_and_rows(const float* w, int64_t O, int64_t I, const Config&
 //   out_i32 != NULL: raw int32 accumulators, row-major [M x N].
 //   out_f32 != NULL: out = acc * row_scale[m * row_stride] * (*col_scale) / n.
 // plan.split > 1 needs `partial` (plan.partial_bytes) and `flags` (kMaxSplitSlots slots
-// that only such launches ever write).
+// that only such launches ever write).  `epoch`: device address of the workspace epoch when
+// the launch tag is to be derived from it (replayable calls), else null.
 hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N, int64_t k_bytes,
                         int64_t pitch, int bits, const GemmPlan& plan, int32_t* partial,
                         unsigned long long* flags, int32_t* out_i32, float* out_f32,
                         const float* row_scale, int row_stride, const float* col_scale, int n,
-                        hipStream_t s, int gemm_stage = -1);
+                        hipStream_t s, int gemm_stage = -1, const unsigned long long* epoch = nullptr);
 
 // Unpack K-contiguous codes [rows x pitch] into one int8 per code.
 //   transpose = 0: out[row * K + k];  transpose = 1: out[k * rows + row].

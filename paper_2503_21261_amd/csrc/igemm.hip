@@ -250,7 +250,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
                         int64_t pitch, int bits, const GemmPlan& plan, int32_t* partial,
                         unsigned long long* flags, int32_t* out_i32, float* out_f32,
                         const float* row_scale, int row_stride, const float* col_scale, int n,
-                        hipStream_t s, int gemm_stage) {
+                        hipStream_t s, int gemm_stage, const unsigned long long* epoch) {
   if (M <= 0 || N <= 0) return hipSuccess;
   GemmArgs g;
   g.A = A;
@@ -263,6 +263,7 @@ hipError_t launch_igemm(const uint8_t* A, const uint8_t* B, int64_t M, int64_t N
   g.partial = partial;
   g.flags = flags;
   g.tag = 0;
+  g.epoch = epoch;
   g.wait_ticks = 0;
   g.row_scale = row_scale;
   g.row_stride = row_stride;

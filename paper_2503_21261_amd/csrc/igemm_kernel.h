@@ -57,6 +57,7 @@ struct GemmArgs {
   int32_t* partial;            // [slot][register image of the 256-thread tile]
   unsigned long long* flags;   // [slot] = tag once the image is complete
   unsigned long long tag;      // 64 bits, never zero, never repeated: slots never need clearing
+  const unsigned long long* epoch;   // replayable calls: the tag is moved by *epoch
   long long wait_ticks;        // bound on the wait for another workgroup's image (100 MHz ticks)
   const float* row_scale;
   int row_stride;
@@ -481,7 +482,7 @@ void igemm_kernel(const GemmArgs g) {
         --zz;
         const int slot = t * (S - 1) + zz;
         if (tid == 0) {
-          const unsigned long long want = g.tag;
+          const unsigned long long want = effective_tag(g.tag, g.epoch);
           const long long start = wall_clock64();
           bool seen;
           do {
@@ -542,7 +543,7 @@ void igemm_kernel(const GemmArgs g) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
       if (tid == 0)
-        __hip_atomic_store(&g.flags[slot], g.tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&g.flags[slot], effective_tag(g.tag, g.epoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }

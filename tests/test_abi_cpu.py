@@ -31,6 +31,7 @@ def test_default_config_is_the_papers():
     hot.lib().hot_default_config(C.byref(cfg))
     assert (cfg.block, cfg.keep, cfg.gx_bits, cfg.gw_bits, cfg.rounding) == (16, 8, 4, 8, 1)
     assert cfg.lqs_threshold == 0.5 and not cfg.keep_idx
+    assert cfg.sample_tokens == 0 and cfg.replayable == 0
     d = hot.Config()
     assert (d.block, d.keep, d.gx_bits, d.gw_bits, d.rounding, d.lqs_threshold) == (16, 8, 4, 8, 1, 0.5)
 
@@ -84,6 +85,18 @@ def test_bad_config_is_an_argument_error(bad):
     st = hot.lib().hot_linear_backward_gx(C.byref(cfg.c()), fake, fake, 64, 64, 64, 1, fake, fake, 1 << 30, None)
     assert st == hot.HOT_ERR_ARG
     assert hot.hot_workspace_bytes(cfg, 64, 64, 64) == 0
+
+
+def test_replayable_is_a_flag():
+    """hot_config.replayable is 0 or 1; anything else is refused before any launch."""
+    cfg = hot.Config().c()
+    fake = C.c_void_p(4096)
+    for value, want in ((2, hot.HOT_ERR_ARG), (-1, hot.HOT_ERR_ARG)):
+        cfg.replayable = value
+        st = hot.lib().hot_linear_backward_gx(C.byref(cfg), fake, fake, 64, 64, 64, 1, fake, fake, 1 << 30, None)
+        assert st == want
+    cfg.replayable = 1      # accepted: the call then fails on its workspace size, still before any launch
+    assert hot.lib().hot_linear_backward_gx(C.byref(cfg), fake, fake, 64, 64, 64, 1, fake, fake, 100, None) == hot.HOT_ERR_WORKSPACE
 
 
 def test_argument_shape_and_workspace_errors_precede_any_launch():

@@ -1118,6 +1118,71 @@ def test_per_sample_tiling_shape_errors_and_gx_is_unaffected():
     check_gx(hot, cfg, gy, w, True, "g_x with sample_tokens set")     # L need not be a multiple of n
 
 
+# ---- calls recorded into a HIP graph ----------------------------------------------------------------
+
+def test_replayable_calls_in_a_hip_graph():
+    """With hot_config.replayable the launch tags come from an epoch in the workspace that every
+    call advances, so a recorded step can be replayed.  One step of configs[0] (compression, both
+    gradients: single-pass exchange kernels, the combined weight / g_y launch and the split-K g_w
+    GEMM, all of which use tags) is captured once and replayed six times on inputs that change
+    between the replays, with eager work and a synchronisation in between; every replay must
+    give the bits of the eager, host-tagged call on the same inputs, and the first also the
+    oracle's.  Half of the replays run with the exchange wait at zero, so that workgroups also
+    take the path that recomputes the other tiles' maxima."""
+    hot = _hot()
+    L, O, I = 512, 768, 768
+    cfg_r = hot.Config(block=16, keep=8, replayable=True)
+    cfg_e = hot.Config(block=16, keep=8)
+    dev = "cuda"
+    xs, ws_, gys = zip(*[make(L, O, I, seed=70 + k, gy_kind=("chan_outlier", "tok_outlier", "normal")[k % 3])
+                         for k in range(7)])
+    x_d, w_d, gy_d = xs[0].to(dev), ws_[0].to(dev), gys[0].to(dev)
+    act_r, work_r = hot.alloc_act_buffer(cfg_r, L, I), hot.alloc_workspace(cfg_r, L, O, I)
+    act_e, work_e = hot.alloc_act_buffer(cfg_e, L, I), hot.alloc_workspace(cfg_e, L, O, I)
+    gx_r, gw_r = torch.empty((L, I), device=dev), torch.empty((O, I), device=dev)
+    gx_e, gw_e = torch.empty((L, I), device=dev), torch.empty((O, I), device=dev)
+
+    def step(cfg, act, work, gx, gw):
+        hot.hot_compress_activation(cfg, x_d, act, work)
+        hot.hot_linear_backward(cfg, gy_d, w_d, act, hot.HOT_Q_PER_TOKEN, gx, gw, work)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # launch plans are made on first use: once before recording
+        step(cfg_r, act_r, work_r, gx_r, gw_r)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(cfg_r, act_r, work_r, gx_r, gw_r)
+    torch.cuda.synchronize()
+    try:
+        for k in range(1, 7):
+            _say(f"[graph] replay {k}")
+            hot.hot_debug_set_exchange_wait_us(0 if k % 2 == 0 else 200)
+            x_d.copy_(xs[k].to(dev)); w_d.copy_(ws_[k].to(dev)); gy_d.copy_(gys[k].to(dev))   # eager work
+            gx_r.fill_(float("nan")); gw_r.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            step(cfg_e, act_e, work_e, gx_e, gw_e)
+            torch.cuda.synchronize()
+            codes_r, sx_r = hot.hot_debug_unpack_activation(cfg_r, act_r, L, I)
+            codes_e, sx_e = hot.hot_debug_unpack_activation(cfg_e, act_e, L, I)
+            assert torch.equal(codes_r, codes_e) and torch.equal(sx_r, sx_e), \
+                f"replay {k}: compressed activation differs from the eager call"
+            assert torch.equal(gx_r, gx_e), f"replay {k}: g_x differs from the eager call"
+            assert torch.equal(gw_r, gw_e), f"replay {k}: g_w differs from the eager call"
+            if k == 1:
+                ref_codes, ref_sx = oracle.compress_activation(xs[k].numpy(), 16, 8)
+                ref_x = oracle.backward_gx(gys[k].numpy(), ws_[k].numpy(), 16, bits=4, per_token=True)
+                ref_w = oracle.backward_gw(gys[k].numpy(), ref_codes, ref_sx, 16, 8)
+                assert_close_maxnorm(gx_r.cpu().numpy(), ref_x["g_x"], "replayed g_x")
+                assert_close_maxnorm(gw_r.cpu().numpy(), ref_w["g_w"], "replayed g_w")
+    finally:
+        hot.hot_debug_set_exchange_wait_us(200)
+
+
 # ---- seeded random shapes and settings ----------------------------------------------------------
 
 def test_seeded_random_shapes_and_settings(exchange_wait, gemm_mode):
