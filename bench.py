@@ -479,12 +479,20 @@ def run_job(torch, hot, hot_inputs, wl, args, want_cpu):
     job = Job(torch, hot, hot_inputs, wl, args)
     ms = job.timed(args.steps, args.warmup)
     # a step recorded into a HIP graph and replayed, for the workloads where launches matter
-    ms_graph = job.timed_graph(args.steps, args.warmup) if (len(job.layers) <= 4 and ms < 5.0) else None
+    ms_graph, graph_error = None, None
+    if len(job.layers) <= 4 and ms < 5.0:
+        try:
+            ms_graph = job.timed_graph(args.steps, args.warmup)
+        except Exception as e:      # context figure only: never lose the measurement over it
+            graph_error = f"{type(e).__name__}: {e}"[:200]
+            torch.cuda.synchronize()
     table = job.kernel_table(max(1, min(args.steps, 5 if len(job.layers) > 8 else 20)))
     layers, finite = job.layer_table()
     res = summarise(job, ms, table, layers, finite, torch)
     if ms_graph is not None:
         res["graph_replay_us_per_step"] = round(ms_graph * 1e3, 2)
+    if graph_error is not None:
+        res["graph_replay_error"] = graph_error
     cpu = None
     if want_cpu:
         cpu = cpu_baseline(job, args.cpu_seconds, args.cpu_sample_tokens or (16384 if len(job.layers) > 1 else 0))
