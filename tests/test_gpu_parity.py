@@ -1183,6 +1183,40 @@ def test_replayable_calls_in_a_hip_graph():
         hot.hot_debug_set_exchange_wait_us(200)
 
 
+def test_replayable_calls_give_the_bits_of_host_tagged_calls():
+    """Every entry point that launches tagged kernels, with tags from the workspace epoch and
+    with tags from the host: the same bits, on a shape whose g_w GEMM splits K and whose
+    transforms take the single-pass kernels (the g_x call twice in a row, so that the second
+    call finds the first one's slots and flags in the workspace)."""
+    hot = _hot()
+    L, O, I = 1024, 768, 512
+    x, w, gy = make(L, O, I, seed=81)
+    xd, wd, gyd = x.cuda(), w.cuda(), gy.cuda()
+    outs = {}
+    for replayable in (False, True):
+        cfg = hot.Config(block=16, keep=8, replayable=replayable)
+        ws = hot.alloc_workspace(cfg, L, O, I)
+        act, wq = hot.alloc_act_buffer(cfg, L, I), hot.alloc_weight_buffer(cfg, O, I)
+        g = {k: torch.empty((L, I), device="cuda") for k in ("gx", "gx2", "cached", "noalloc", "both_x")}
+        gw, gw2 = torch.empty((O, I), device="cuda"), torch.empty((O, I), device="cuda")
+        hot.hot_compress_activation(cfg, xd, act, ws)
+        hot.hot_linear_backward_gx(cfg, gyd, wd, hot.HOT_Q_PER_TOKEN, g["gx"], ws)
+        hot.hot_linear_backward_gx(cfg, gyd, wd, hot.HOT_Q_PER_TENSOR, g["gx2"], ws)
+        hot.hot_quantize_weight(cfg, wd, wq, ws)
+        hot.hot_linear_backward_gx_cached(cfg, gyd, wq, I, hot.HOT_Q_PER_TOKEN, g["cached"], ws)
+        hot.hot_linear_backward_gx_noalloc(cfg, gyd, wd, hot.HOT_Q_PER_TOKEN, g["noalloc"])
+        hot.hot_linear_backward_gw(cfg, gyd, act, I, gw, ws)
+        hot.hot_linear_backward(cfg, gyd, wd, act, hot.HOT_Q_PER_TOKEN, g["both_x"], gw2, ws)
+        torch.cuda.synchronize()
+        outs[replayable] = {**{k: v.cpu() for k, v in g.items()}, "gw": gw.cpu(), "gw2": gw2.cpu()}
+    for k in outs[False]:
+        assert torch.equal(outs[False][k], outs[True][k]), f"{k}: replayable call differs from the host-tagged call"
+    assert torch.equal(outs[True]["gx"], outs[True]["cached"]) and torch.equal(outs[True]["gx"], outs[True]["noalloc"])
+    assert torch.equal(outs[True]["gx"], outs[True]["both_x"]) and torch.equal(outs[True]["gw"], outs[True]["gw2"])
+    ref = oracle.backward_gx(gy.numpy(), w.numpy(), 16, bits=4, per_token=True)
+    assert_close_maxnorm(outs[True]["gx"].numpy(), ref["g_x"], "replayable g_x")
+
+
 # ---- seeded random shapes and settings ----------------------------------------------------------
 
 def test_seeded_random_shapes_and_settings(exchange_wait, gemm_mode):
