@@ -27,14 +27,20 @@ def _say(*a):
     sys.stdout.flush()
 
 
-def assert_close_maxnorm(got, ref, what):
-    """The stated bound, 1e-5 of max|ref| on every element, and an element-wise one that also
-    holds small entries to their own size: |got - ref| <= 1e-5 |ref| + 1e-6 max|ref| (the
-    epilogue's own error is about 2e-7 relative: one int->float conversion, two multiplies)."""
+def assert_close_maxnorm(got, ref, what, exact_accumulators=True):
+    """The stated bound, 1e-5 of max|ref| on every element, and, where the accumulators are
+    exact integers, an element-wise one that also holds small entries to their own size:
+    |got - ref| <= 1e-5 |ref| + 1e-6 max|ref| (the epilogue's own error is about 2e-7 relative:
+    one int->float conversion, two multiplies).  The bfloat16 variant sums its products in fp32
+    on the matrix cores: an entry that is a small sum of K large cancelling terms (outlier
+    tokens) carries an error of up to K 2^-24 of the terms' magnitude, not of its own, so only
+    the stated max-norm bound applies there."""
     denom = np.max(np.abs(ref))
     diff = np.abs(got.astype(np.float64) - ref)
     err = np.max(diff)
     assert err <= REL_TOL * denom + 1e-300, f"{what}: max err {err:.3e} vs max|ref| {denom:.3e}"
+    if not exact_accumulators:
+        return
     excess = diff - (REL_TOL * np.abs(ref) + 1e-6 * denom)
     worst = np.unravel_index(np.argmax(excess), excess.shape)
     assert excess[worst] <= 0, (f"{what}: element {worst}: got {got[worst]!r}, ref {ref[worst]!r}, "
@@ -1039,8 +1045,8 @@ def check_gw_bf16(hot, cfg, gy, x, what):
     assert np.array_equal(codes.cpu().numpy().view(np.uint16), xb_ref), f"{what}: bf16 activation differs"
     assert np.array_equal(taps["qg"].cpu().numpy().view(np.uint16), ref["gh_bits"]), f"{what}: bf16 HLA(g_y) differs"
     assert sx.item() == 1.0 and taps["sg"].item() == 1.0
-    assert_close_maxnorm(taps["acc"].cpu().numpy(), ref["g_w"] * n, what + " accumulators")
-    assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w")
+    assert_close_maxnorm(taps["acc"].cpu().numpy(), ref["g_w"] * n, what + " accumulators", exact_accumulators=False)
+    assert_close_maxnorm(gw.cpu().numpy(), ref["g_w"], what + " g_w", exact_accumulators=False)
     Lr = cfg.reduced_tokens(L)
     assert hot.hot_act_buffer_bytes(cfg, L, I) == 256 + I * ((2 * Lr + 127) // 128 * 128)
     return ref, gw
