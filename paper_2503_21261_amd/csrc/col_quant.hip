@@ -38,10 +38,12 @@ ColPlan plan_col(int64_t nblk, int64_t C, int n, int r, int bits, bool lowpass_d
   const int vdiv = (C % 4 == 0) ? 4 : (C % 2 == 0 ? 2 : 1);
   auto tiles = [&](int vec, int kbw) { return ceil_div(C, 64 * vec) * ceil_div(nblk, 4 * kbw); };
   // Abs-max pass (a workgroup tile is 256 * vec columns x kbw blocks): about 64 rows per
-  // wave and visit, two or four columns per lane; smaller tiles while the 256 compute units
-  // would otherwise be short of workgroups, narrower ones for narrow tensors.
+  // wave and visit, two columns per lane (measured on MI355X for 16-row blocks: 556 us with
+  // two against 580-596 us with four on 3.3 GB, 119 against 123 us on 620 MB, one column
+  // 124 us); smaller tiles while the 256 compute units would otherwise be short of
+  // workgroups, narrower ones for narrow tensors.
   auto tiles_a = [&](int vec, int kbw) { return ceil_div(C, 256 * vec) * ceil_div(nblk, kbw); };
-  const int vpref = n == 16 ? 4 : 2;
+  const int vpref = 2;
   p.vec_a = vdiv < vpref ? vdiv : vpref;
   while (p.vec_a > 1 && C < 256 * p.vec_a) p.vec_a /= 2;
   p.kbw_a = n >= 64 ? 1 : 64 / n;
